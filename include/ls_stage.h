@@ -1,0 +1,229 @@
+/*
+ * ls_stage.h -- C ABI of the execute-while-load pipeline-stage executor (MI355X / gfx950).
+ *
+ * One ls_stage is one stage of an execution pipeline in the sense of the paper's
+ * Section 4.1: it holds a contiguous span [layer_lo, layer_hi) of a decoder's model
+ * blocks, takes the previous stage's intermediate result (or token ids, if it is the
+ * first stage), produces its own intermediate result (or next-token ids, if it is the
+ * last stage) and keeps its own KV cache, which never leaves the stage.  The model
+ * arrives as packed blocks (Section 5, "tensor packing": one contiguous region per
+ * block; "GPU memory pre-allocation": all block and intermediate buffers are sized once),
+ * and a layer may run as soon as its own block has landed in device memory
+ * (execute-while-load: Sections 1, 3 and 7.3), whatever has or has not arrived of the
+ * later layers.  The per-layer arithmetic is the Llama-2 pre-norm decoder block that the
+ * paper's Section 6 takes over from Meta's Llama inference code:
+ *
+ *     y = RMSNorm(x; g_attn)          q,k,v = y Wqkv^T        RoPE(q), RoPE(k)
+ *     append k,v to the cache         o = causal softmax(q k^T / sqrt(hd)) v   (GQA)
+ *     x += o Wo^T                     y = RMSNorm(x; g_ffn)
+ *     x += (silu(y Wg^T) * (y Wu^T)) Wd^T
+ *
+ * Conventions
+ *   - "device" pointers are HIP device memory owned by the caller; "host" pointers are
+ *     ordinary host memory unless "pinned" is stated.  The library never frees or
+ *     reallocates a caller buffer.  After ls_stage_create it allocates no device memory.
+ *   - hip_stream arguments are a hipStream_t passed as void* (NULL = the null stream).
+ *   - Every call only enqueues work; none waits for the GPU.
+ *   - Every function returns LS_OK (0) or a negative ls_status.  An error that can be
+ *     seen from the host arguments is reported before anything is enqueued, so a failing
+ *     call has no device side effects.  ls_last_error() gives a thread-local message.
+ *   - Matrices are row-major [out, in].  Activations are row-major [rows, hidden].
+ *   - dtype 0 = IEEE fp32, 1 = bfloat16 (16-bit patterns, round-to-nearest-even).
+ */
+#ifndef LS_STAGE_H
+#define LS_STAGE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define LS_ABI_VERSION 1u
+#define LS_DTYPE_F32 0u
+#define LS_DTYPE_BF16 1u
+
+/* Block index of the embedding table; the head block has index n_layers_total. */
+#define LS_BLOCK_EMBED (-1)
+
+typedef struct ls_stage ls_stage; /* opaque */
+
+typedef enum {
+  LS_OK = 0,
+  LS_ERR_INVALID_ARG = -1,    /* null pointer, bad size, unsupported shape             */
+  LS_ERR_BLOCK_RANGE = -2,    /* block index is not one this stage holds               */
+  LS_ERR_NOT_LOADED = -3,     /* a block the call needs has not been enqueued for load */
+  LS_ERR_ALREADY_LOADED = -4, /* block was already enqueued since the last reset       */
+  LS_ERR_KV_OVERFLOW = -5,    /* a sequence would outgrow max_seq                      */
+  LS_ERR_OOM = -6,            /* a caller buffer is smaller than the sizing query says */
+  LS_ERR_HIP = -7             /* a HIP runtime call failed; see ls_last_error()        */
+} ls_status;
+
+/* Shape of the decoder and the limits all buffers are sized for. */
+typedef struct {
+  uint32_t abi_version;    /* LS_ABI_VERSION                                          */
+  uint32_t dtype;          /* storage type of weights, hidden states and KV cache     */
+  uint32_t n_layers_total; /* layers of the whole model (the stage holds a sub-span)  */
+  uint32_t hidden;         /* d                                                       */
+  uint32_t n_q_heads;      /* Hq                                                      */
+  uint32_t n_kv_heads;     /* Hkv, divides Hq; query head h reads kv head h/(Hq/Hkv)  */
+  uint32_t head_dim;       /* hd, even; 64 or 128 for the bf16 fast kernels           */
+  uint32_t ffn;            /* F                                                       */
+  uint32_t vocab;          /* V; 0 = the model has no embedding and no LM head block  */
+  float rms_eps;           /* added to the mean of squares inside the square root     */
+  float rope_base;         /* pair i of a head turns by pos * rope_base^(-2i/hd)      */
+  uint32_t max_batch;      /* most sequences in one call                              */
+  uint32_t max_seq;        /* most cached positions per sequence                      */
+  uint32_t max_tokens;     /* most rows in one prefill call (>= max_batch)            */
+} ls_cfg;
+
+/*
+ * KV cache of one stage; all three buffers are device memory owned by the caller
+ * (Section 5 leaves runtime state of dynamic size to the serving engine).
+ *   k, v      [layer_hi-layer_lo][max_batch][n_kv_heads][max_seq][head_dim], dtype
+ *   seq_lens  [max_batch] int32: positions already cached per sequence.  Prefill sets
+ *             it, decode adds one, both on the device at the end of the call.
+ */
+typedef struct {
+  void* k;
+  void* v;
+  int32_t* seq_lens;
+} ls_kv;
+
+/* ---- packed block format (pure functions of the shape; no device access) ------------
+ *
+ * Section 5: all tensors of a block lie in one contiguous region, so a block moves with
+ * one bulk copy; the layout has no effect on what is computed.  A decoder layer's block
+ * holds, in this order, each tensor starting on a 256-byte boundary:
+ *   0 attn_norm [d]   1 wqkv [(Hq+2Hkv)*hd, d] (query rows, then key rows, then value rows)
+ *   2 wo [d, Hq*hd]   3 ffn_norm [d]   4 wgu [2F, d] (gate rows, then up rows)   5 wd [d, F]
+ * block LS_BLOCK_EMBED: 0 embed [V, d].   block n_layers_total: 0 final_norm [d], 1 lm_head [V, d].
+ */
+
+/* Bytes of block `layer`; 0 if the shape or the index is invalid. */
+size_t ls_block_bytes(const ls_cfg* cfg, int layer);
+
+/* Number of tensors in block `layer` (6, 1 or 2); 0 if invalid. */
+int ls_block_tensor_count(const ls_cfg* cfg, int layer);
+
+/* Byte offset and byte size of tensor `index` inside block `layer`. */
+ls_status ls_block_tensor(const ls_cfg* cfg, int layer, int index, size_t* offset, size_t* bytes);
+
+/* ---- sizing queries (pure) -----------------------------------------------------------*/
+
+/* Device bytes for the weight slab holding every block of the stage [lo, hi), including
+ * the embedding block if lo == 0 and the head block if hi == n_layers_total (vocab > 0). */
+size_t ls_stage_slab_bytes(const ls_cfg* cfg, int layer_lo, int layer_hi);
+
+/* Device bytes for the intermediate results of one call at the cfg's limits. */
+size_t ls_stage_workspace_bytes(const ls_cfg* cfg, int layer_lo, int layer_hi);
+
+/* Device bytes of EACH of ls_kv.k and ls_kv.v. */
+size_t ls_stage_kv_bytes(const ls_cfg* cfg, int layer_lo, int layer_hi);
+
+/* ---- life cycle ----------------------------------------------------------------------*/
+
+/*
+ * Create the stage [layer_lo, layer_hi), 0 <= lo < hi <= n_layers_total, on the current
+ * HIP device.  weight_slab and workspace are device buffers of at least the sizes the
+ * queries above return (else LS_ERR_OOM), 256-byte aligned, owned by the caller, and must
+ * outlive the stage.  The stage owns only host metadata and HIP events.  All blocks start
+ * NOT LOADED.  *out is written only on success.
+ */
+ls_status ls_stage_create(const ls_cfg* cfg, int layer_lo, int layer_hi, void* weight_slab,
+                          size_t slab_bytes, void* workspace, size_t ws_bytes, ls_stage** out);
+
+/* Release the handle and its events.  Does not wait for enqueued work: synchronise first. */
+void ls_stage_destroy(ls_stage* stage);
+
+/* Packed size of block `layer` of this stage (0 if the stage does not hold it). */
+size_t ls_stage_block_bytes(const ls_stage* stage, int layer);
+
+/* ---- the loader (execute-while-load) -------------------------------------------------*/
+
+/*
+ * Enqueue the copy of one packed block from host memory into its place in the slab on
+ * hip_stream (the "copy stream"), then record the block's event there.  host_ptr must hold
+ * ls_stage_block_bytes(stage, layer) bytes, be pinned for the copy to be asynchronous, and
+ * stay valid until the event has completed.  Blocks may arrive in any order (the paper's
+ * Algorithm 1 hands sub-groups circularly shifted orders).  `layer` is a decoder layer in
+ * [lo, hi), LS_BLOCK_EMBED (first stage) or n_layers_total (last stage), else
+ * LS_ERR_BLOCK_RANGE.  A second load of a block without ls_stage_reset_blocks in between
+ * is LS_ERR_ALREADY_LOADED.
+ */
+ls_status ls_stage_load_block(ls_stage* stage, const void* host_ptr, int layer, void* hip_stream);
+
+/* Mark `layer`'s block as loaded without copying: the caller has already placed the
+ * packed bytes at ls_stage_block_device_ptr() and ordered that write before hip_stream's
+ * current tail (the hot-start case of Section 5, model already in GPU memory). */
+ls_status ls_stage_adopt_block(ls_stage* stage, int layer, void* hip_stream);
+
+/* Device address of block `layer` inside the slab (NULL if the stage does not hold it). */
+void* ls_stage_block_device_ptr(const ls_stage* stage, int layer);
+
+/* Forget which blocks are loaded (all become NOT LOADED); the slab is not touched.  The
+ * caller must have synchronised with every call that still uses the old blocks. */
+ls_status ls_stage_reset_blocks(ls_stage* stage);
+
+/* ---- the forward pass ----------------------------------------------------------------*/
+
+/*
+ * Prompt pass over `batch` sequences packed row after row without padding.
+ *   in               device.  First stage of a model with vocab>0: int32 token ids
+ *                    [total_tokens]; otherwise hidden states [total_tokens, hidden], dtype.
+ *   cu_seqlens_dev   device int32 [batch+1], row offsets: sequence b owns rows
+ *                    [cu[b], cu[b+1]) at positions 0..len_b-1; cu[0]=0, cu[batch]=total_tokens.
+ *   cu_seqlens_host  host copy of the same array (used for validation and launch sizing).
+ *   kv               this stage's cache; positions [0,len_b) of every layer are written,
+ *                    seq_lens[b] = len_b for b < batch.
+ *   out              device.  Last stage of a model with vocab>0: int32 next-token ids
+ *                    [batch] (greedy, lowest index wins ties) taken at the last row of each
+ *                    sequence; otherwise the residual stream after the stage's last layer,
+ *                    [total_tokens, hidden], dtype, not normalised.
+ *   logits_out       optional device fp32 [batch, vocab] (last stage only), or NULL.
+ * Each layer's kernels are ordered after that layer's block event (the gate).  Every block
+ * the stage holds must already have been enqueued by ls_stage_load_block (or adopted),
+ * else LS_ERR_NOT_LOADED.  Errors: batch/total_tokens/len beyond the cfg limits
+ * (LS_ERR_INVALID_ARG, LS_ERR_KV_OVERFLOW).
+ */
+ls_status ls_stage_prefill(ls_stage* stage, const void* in, const int32_t* cu_seqlens_dev,
+                           const int32_t* cu_seqlens_host, int batch, int total_tokens,
+                           const ls_kv* kv, void* out, float* logits_out, void* hip_stream);
+
+/*
+ * One generation step: one new row per sequence at position seq_lens[b], appended to the
+ * cache; attends to positions 0..seq_lens[b].
+ *   in        device: int32 [batch] token ids (first stage) or hidden [batch, hidden].
+ *   max_ctx   host-side upper bound of seq_lens[b] over the batch before this step;
+ *             max_ctx + 1 > max_seq is LS_ERR_KV_OVERFLOW.  (A sequence whose device-side
+ *             length is already max_seq is left untouched by the kernels.)
+ *   out / logits_out as in prefill with one row per sequence.
+ */
+ls_status ls_stage_decode(ls_stage* stage, const void* in, int batch, int max_ctx,
+                          const ls_kv* kv, void* out, float* logits_out, void* hip_stream);
+
+/* ---- measurement ---------------------------------------------------------------------*/
+
+/* With profiling on, ls_stage_load_block brackets each copy and ls_stage_prefill brackets
+ * each layer with HIP events (default off). */
+ls_status ls_stage_set_profiling(ls_stage* stage, int on);
+
+/*
+ * After the caller has synchronised: per decoder layer of the stage (n <= hi-lo entries),
+ * copy_ms[i]    = duration of layer lo+i's last block copy,
+ * compute_ms[i] = duration of layer lo+i's kernels in the last prefill call,
+ * copy_end_ms[i] / compute_end_ms[i] = completion times relative to the first recorded
+ * event of the last load / prefill sequence (either pair may be NULL).
+ * LS_ERR_INVALID_ARG if profiling was off or nothing was recorded.
+ */
+ls_status ls_stage_layer_times(ls_stage* stage, float* copy_ms, float* compute_ms,
+                               float* copy_end_ms, float* compute_end_ms, int n);
+
+/* Message of the last failing call on this thread ("" if none). */
+const char* ls_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LS_STAGE_H */

@@ -1,0 +1,18 @@
+// Shape-based choice between the kernels of one operator.  fp32 always takes the generic
+// kernels; bf16 takes an MFMA kernel wherever its shape constraints hold.
+#include "kernels.hpp"
+
+namespace ls {
+
+void launch_gemm(uint32_t dt, Epilogue epi, const void* A, const void* W, int M, int N, int K, void* out,
+                 float* resid, hipStream_t st) {
+  launch_gemm_generic(dt, epi, A, W, M, N, K, out, resid, st);
+}
+
+void launch_attention(uint32_t dt, const void* qkv, int qkv_stride, const void* kcache, const void* vcache,
+                      const int32_t* row_seq, const int32_t* row_pos, int rows, int hq, int hkv, int hd,
+                      int max_seq, void* out, hipStream_t st) {
+  launch_attention_generic(dt, qkv, qkv_stride, kcache, vcache, row_seq, row_pos, rows, hq, hkv, hd, max_seq, out, st);
+}
+
+}  // namespace ls

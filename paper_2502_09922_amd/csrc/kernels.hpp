@@ -1,0 +1,64 @@
+// Internal launcher interface between the stage runtime and the HIP kernels (gfx950).
+// Every launcher only enqueues on `st`; shapes are validated by the runtime before.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace ls {
+
+enum : uint32_t { F32 = 0, BF16 = 1 };
+
+// What a GEMM does with its fp32 accumulators.
+enum Epilogue : int {
+  EPI_STORE = 0,   // out[M,N] in dtype
+  EPI_RESID = 1,   // resid[M,N] (fp32) += acc
+  EPI_SWIGLU = 2,  // W is [2N,K] (gate rows then up rows); out[M,N] = silu(gate) * up, dtype
+  EPI_F32 = 3      // out[M,N] fp32
+};
+
+// row_seq[r] / row_pos[r]: sequence and cache position of every row of a call.
+void launch_row_index_prefill(const int32_t* cu_seqlens, int batch, int total, int32_t* row_seq,
+                              int32_t* row_pos, int32_t* last_rows, hipStream_t st);
+// Decode: row b is sequence b at position seq_lens[b]; -1 marks a row that has no room left.
+void launch_row_index_decode(const int32_t* seq_lens, int batch, int max_seq, int32_t* row_seq,
+                             int32_t* row_pos, int32_t* last_rows, hipStream_t st);
+void launch_seq_lens_set(const int32_t* cu_seqlens, int batch, int32_t* seq_lens, hipStream_t st);
+void launch_seq_lens_inc(int batch, int max_seq, int32_t* seq_lens, hipStream_t st);
+
+void launch_embed(uint32_t dt, const void* table, const int32_t* tok, float* x, int rows, int d,
+                  int vocab, hipStream_t st);
+void launch_load_hidden(uint32_t dt, const void* in, float* x, size_t n, hipStream_t st);
+void launch_store_hidden(uint32_t dt, const float* x, void* out, size_t n, hipStream_t st);
+
+// y[r,:] = x[map ? map[r] : r, :] / sqrt(mean(x^2) + eps) * gamma
+void launch_rmsnorm(uint32_t dt, const float* x, const void* gamma, void* y, int rows, int d,
+                    float eps, const int32_t* row_map, hipStream_t st);
+
+// C = A[M,K] * W[N,K]^T with fp32 accumulation; A, W in dtype.
+void launch_gemm(uint32_t dt, Epilogue epi, const void* A, const void* W, int M, int N, int K,
+                 void* out, float* resid, hipStream_t st);
+
+void launch_gemm_generic(uint32_t dt, Epilogue epi, const void* A, const void* W, int M, int N, int K,
+                         void* out, float* resid, hipStream_t st);
+
+// Rotate q (in place inside qkv) and k by the per-position cos/sin table, write k and v
+// into the cache at [seq][kv head][pos].  qkv is [rows, (Hq+2Hkv)*hd].
+void launch_rope_append(uint32_t dt, void* qkv, const float* cs_table, const int32_t* row_seq,
+                        const int32_t* row_pos, int rows, int hq, int hkv, int hd, int max_seq,
+                        void* kcache, void* vcache, hipStream_t st);
+
+// Causal attention of every row against its sequence's cache positions 0..row_pos[r].
+// q is read from qkv ([rows, qkv_stride]); out is [rows, Hq*hd].
+void launch_attention(uint32_t dt, const void* qkv, int qkv_stride, const void* kcache,
+                      const void* vcache, const int32_t* row_seq, const int32_t* row_pos, int rows,
+                      int hq, int hkv, int hd, int max_seq, void* out, hipStream_t st);
+
+void launch_attention_generic(uint32_t dt, const void* qkv, int qkv_stride, const void* kcache,
+                              const void* vcache, const int32_t* row_seq, const int32_t* row_pos, int rows,
+                              int hq, int hkv, int hd, int max_seq, void* out, hipStream_t st);
+
+// tok[r] = index of the largest logit of row r, lowest index on ties.
+void launch_argmax(const float* logits, int rows, int vocab, int32_t* tok, hipStream_t st);
+
+}  // namespace ls

@@ -1,0 +1,486 @@
+// Stage runtime behind the C ABI of include/ls_stage.h: block table, event-gated loader,
+// workspace carving and the per-layer launch sequence.  Host code only; every device step
+// is a kernel launched through kernels.hpp.
+#include "../../include/ls_stage.h"
+#include "kernels.hpp"
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+ls_status fail(ls_status code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof g_err, fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+#define LS_HIP(call)                                                                      \
+  do {                                                                                    \
+    hipError_t e_ = (call);                                                               \
+    if (e_ != hipSuccess) return fail(LS_ERR_HIP, "%s: %s", #call, hipGetErrorString(e_)); \
+  } while (0)
+
+constexpr size_t ALIGN = 256;
+inline size_t up(size_t n) { return (n + ALIGN - 1) / ALIGN * ALIGN; }
+inline size_t isz(const ls_cfg* c) { return c->dtype == LS_DTYPE_F32 ? 4 : 2; }
+
+bool cfg_ok(const ls_cfg* c) {
+  if (!c) return false;
+  if (c->abi_version != LS_ABI_VERSION || c->dtype > LS_DTYPE_BF16) return false;
+  if (!c->n_layers_total || !c->hidden || !c->n_q_heads || !c->n_kv_heads || !c->head_dim || !c->ffn) return false;
+  if (c->n_q_heads % c->n_kv_heads) return false;
+  if ((c->head_dim & 1) || c->head_dim > 256) return false;
+  if (!c->max_batch || !c->max_seq || c->max_tokens < c->max_batch) return false;
+  if (!(c->rms_eps >= 0.f) || !(c->rope_base > 0.f)) return false;
+  // 32-bit row*column products inside kernels stay in range
+  if ((uint64_t)c->max_tokens > (1u << 30) || (uint64_t)c->max_seq > (1u << 24)) return false;
+  return true;
+}
+
+// ---- packed block format ----------------------------------------------------------------
+struct TensorSpan { size_t off, bytes; };
+
+// Fills spans (if non-null) and returns the tensor count of block `layer`, 0 if invalid.
+int block_tensors(const ls_cfg* c, int layer, TensorSpan* spans, size_t* total) {
+  if (!cfg_ok(c)) return 0;
+  const size_t e = isz(c), d = c->hidden, hd = c->head_dim, F = c->ffn, V = c->vocab;
+  size_t elems[6];
+  int n = 0;
+  if (layer >= 0 && layer < (int)c->n_layers_total) {
+    elems[n++] = d;
+    elems[n++] = (size_t)(c->n_q_heads + 2 * c->n_kv_heads) * hd * d;
+    elems[n++] = d * (size_t)c->n_q_heads * hd;
+    elems[n++] = d;
+    elems[n++] = 2 * F * d;
+    elems[n++] = d * F;
+  } else if (layer == LS_BLOCK_EMBED && V) {
+    elems[n++] = V * d;
+  } else if (layer == (int)c->n_layers_total && V) {
+    elems[n++] = d;
+    elems[n++] = V * d;
+  } else {
+    return 0;
+  }
+  size_t off = 0;
+  for (int i = 0; i < n; ++i) {
+    if (spans) spans[i] = {off, elems[i] * e};
+    off = up(off + elems[i] * e);
+  }
+  if (total) *total = off;
+  return n;
+}
+
+bool span_ok(const ls_cfg* c, int lo, int hi) {
+  return cfg_ok(c) && lo >= 0 && lo < hi && hi <= (int)c->n_layers_total;
+}
+
+// ---- workspace carving ------------------------------------------------------------------
+struct Carve {
+  size_t cs, x, y, qkv, attn, h, logits, row_seq, row_pos, last_rows, next_tok, total;
+};
+
+Carve carve(const ls_cfg* c, int lo, int hi) {
+  Carve w{};
+  const size_t e = isz(c), T = c->max_tokens, B = c->max_batch, d = c->hidden;
+  const size_t qkv_cols = (size_t)(c->n_q_heads + 2 * c->n_kv_heads) * c->head_dim;
+  const bool last = c->vocab && hi == (int)c->n_layers_total;
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off = up(off + bytes); return o; };
+  w.cs = take((size_t)c->max_seq * (c->head_dim / 2) * 2 * sizeof(float));
+  w.x = take(T * d * sizeof(float));
+  w.y = take(T * d * e);
+  w.qkv = take(T * qkv_cols * e);
+  w.attn = take(T * (size_t)c->n_q_heads * c->head_dim * e);
+  w.h = take(T * (size_t)c->ffn * e);
+  w.logits = take(last ? B * (size_t)c->vocab * sizeof(float) : 0);
+  w.row_seq = take(T * sizeof(int32_t));
+  w.row_pos = take(T * sizeof(int32_t));
+  w.last_rows = take(B * sizeof(int32_t));
+  w.next_tok = take(B * sizeof(int32_t));
+  (void)lo;
+  w.total = off;
+  return w;
+}
+
+enum BlockState { NOT_LOADED = 0, ENQUEUED = 1 };
+
+struct Block {
+  int layer;
+  size_t off, bytes;
+  int state;
+  bool timed;  // copy_start / loaded bracket a copy made with profiling on
+  hipEvent_t copy_start, loaded;
+};
+
+}  // namespace
+
+struct ls_stage {
+  ls_cfg cfg;
+  int lo, hi;
+  bool first, last;
+  char* slab;
+  char* ws;
+  Carve w;
+  std::vector<Block> blocks;  // [embed?] layers lo..hi-1 [head?]
+  int layer0;                 // index in blocks of layer lo
+  bool profiling;
+  bool compute_timed;
+  int origin_block;  // first block copied with profiling on since the last reset, or -1
+  std::vector<hipEvent_t> comp_start, comp_end;
+
+  Block* find(int layer) {
+    for (auto& b : blocks)
+      if (b.layer == layer) return &b;
+    return nullptr;
+  }
+  const Block* find(int layer) const { return const_cast<ls_stage*>(this)->find(layer); }
+};
+
+extern "C" {
+
+const char* ls_last_error(void) { return g_err; }
+
+size_t ls_block_bytes(const ls_cfg* cfg, int layer) {
+  size_t total = 0;
+  return block_tensors(cfg, layer, nullptr, &total) ? total : 0;
+}
+
+int ls_block_tensor_count(const ls_cfg* cfg, int layer) { return block_tensors(cfg, layer, nullptr, nullptr); }
+
+ls_status ls_block_tensor(const ls_cfg* cfg, int layer, int index, size_t* offset, size_t* bytes) {
+  TensorSpan sp[6];
+  int n = block_tensors(cfg, layer, sp, nullptr);
+  if (!n) return fail(LS_ERR_INVALID_ARG, "ls_block_tensor: invalid shape or block index %d", layer);
+  if (index < 0 || index >= n || !offset || !bytes)
+    return fail(LS_ERR_INVALID_ARG, "ls_block_tensor: tensor index %d outside [0,%d)", index, n);
+  *offset = sp[index].off;
+  *bytes = sp[index].bytes;
+  return LS_OK;
+}
+
+size_t ls_stage_slab_bytes(const ls_cfg* cfg, int lo, int hi) {
+  if (!span_ok(cfg, lo, hi)) return 0;
+  size_t total = 0;
+  if (cfg->vocab && lo == 0) total += ls_block_bytes(cfg, LS_BLOCK_EMBED);
+  for (int l = lo; l < hi; ++l) total += ls_block_bytes(cfg, l);
+  if (cfg->vocab && hi == (int)cfg->n_layers_total) total += ls_block_bytes(cfg, hi);
+  return total;
+}
+
+size_t ls_stage_workspace_bytes(const ls_cfg* cfg, int lo, int hi) {
+  return span_ok(cfg, lo, hi) ? carve(cfg, lo, hi).total : 0;
+}
+
+size_t ls_stage_kv_bytes(const ls_cfg* cfg, int lo, int hi) {
+  if (!span_ok(cfg, lo, hi)) return 0;
+  return (size_t)(hi - lo) * cfg->max_batch * cfg->n_kv_heads * cfg->max_seq * cfg->head_dim * isz(cfg);
+}
+
+ls_status ls_stage_create(const ls_cfg* cfg, int lo, int hi, void* weight_slab, size_t slab_bytes,
+                          void* workspace, size_t ws_bytes, ls_stage** out) {
+  if (!out) return fail(LS_ERR_INVALID_ARG, "ls_stage_create: out is NULL");
+  if (!cfg_ok(cfg)) return fail(LS_ERR_INVALID_ARG, "ls_stage_create: invalid ls_cfg");
+  if (!span_ok(cfg, lo, hi)) return fail(LS_ERR_BLOCK_RANGE, "ls_stage_create: span [%d,%d) invalid", lo, hi);
+  if (!weight_slab || !workspace) return fail(LS_ERR_INVALID_ARG, "ls_stage_create: NULL buffer");
+  if (((uintptr_t)weight_slab | (uintptr_t)workspace) & (ALIGN - 1))
+    return fail(LS_ERR_INVALID_ARG, "ls_stage_create: buffers must be 256-byte aligned");
+  if (slab_bytes < ls_stage_slab_bytes(cfg, lo, hi)) return fail(LS_ERR_OOM, "ls_stage_create: weight slab too small");
+  Carve w = carve(cfg, lo, hi);
+  if (ws_bytes < w.total) return fail(LS_ERR_OOM, "ls_stage_create: workspace too small");
+
+  ls_stage* s = new (std::nothrow) ls_stage();
+  if (!s) return fail(LS_ERR_OOM, "ls_stage_create: host allocation failed");
+  s->cfg = *cfg;
+  s->lo = lo;
+  s->hi = hi;
+  s->first = cfg->vocab && lo == 0;
+  s->last = cfg->vocab && hi == (int)cfg->n_layers_total;
+  s->slab = (char*)weight_slab;
+  s->ws = (char*)workspace;
+  s->w = w;
+  s->profiling = false;
+  s->compute_timed = false;
+  s->origin_block = -1;
+
+  size_t off = 0;
+  auto add = [&](int layer) {
+    Block b{};
+    b.layer = layer;
+    b.off = off;
+    b.bytes = ls_block_bytes(cfg, layer);
+    b.state = NOT_LOADED;
+    off += b.bytes;
+    s->blocks.push_back(b);
+  };
+  if (s->first) add(LS_BLOCK_EMBED);
+  s->layer0 = (int)s->blocks.size();
+  for (int l = lo; l < hi; ++l) add(l);
+  if (s->last) add(hi);
+
+  auto cleanup = [&]() {
+    for (auto& b : s->blocks) {
+      if (b.copy_start) (void)hipEventDestroy(b.copy_start);
+      if (b.loaded) (void)hipEventDestroy(b.loaded);
+    }
+    for (auto e : s->comp_start) (void)hipEventDestroy(e);
+    for (auto e : s->comp_end) (void)hipEventDestroy(e);
+    delete s;
+  };
+  for (auto& b : s->blocks) {
+    if (hipEventCreate(&b.copy_start) != hipSuccess || hipEventCreate(&b.loaded) != hipSuccess) {
+      cleanup();
+      return fail(LS_ERR_HIP, "ls_stage_create: hipEventCreate failed");
+    }
+  }
+  for (int l = lo; l < hi; ++l) {
+    hipEvent_t a = nullptr, b = nullptr;
+    if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) {
+      if (a) (void)hipEventDestroy(a);
+      cleanup();
+      return fail(LS_ERR_HIP, "ls_stage_create: hipEventCreate failed");
+    }
+    s->comp_start.push_back(a);
+    s->comp_end.push_back(b);
+  }
+
+  // cos/sin of pos * base^(-2i/hd), evaluated in double and stored as fp32 pairs
+  const int half = cfg->head_dim / 2;
+  std::vector<float> cs((size_t)cfg->max_seq * half * 2);
+  for (uint32_t p = 0; p < cfg->max_seq; ++p)
+    for (int i = 0; i < half; ++i) {
+      double a = (double)p * std::pow((double)cfg->rope_base, -2.0 * i / (double)cfg->head_dim);
+      cs[((size_t)p * half + i) * 2] = (float)std::cos(a);
+      cs[((size_t)p * half + i) * 2 + 1] = (float)std::sin(a);
+    }
+  hipError_t e = hipMemcpy(s->ws + w.cs, cs.data(), cs.size() * sizeof(float), hipMemcpyHostToDevice);
+  if (e != hipSuccess) {
+    cleanup();
+    return fail(LS_ERR_HIP, "ls_stage_create: table upload: %s", hipGetErrorString(e));
+  }
+  *out = s;
+  return LS_OK;
+}
+
+void ls_stage_destroy(ls_stage* s) {
+  if (!s) return;
+  for (auto& b : s->blocks) {
+    (void)hipEventDestroy(b.copy_start);
+    (void)hipEventDestroy(b.loaded);
+  }
+  for (auto e : s->comp_start) (void)hipEventDestroy(e);
+  for (auto e : s->comp_end) (void)hipEventDestroy(e);
+  delete s;
+}
+
+size_t ls_stage_block_bytes(const ls_stage* s, int layer) {
+  if (!s) return 0;
+  const Block* b = s->find(layer);
+  return b ? b->bytes : 0;
+}
+
+void* ls_stage_block_device_ptr(const ls_stage* s, int layer) {
+  if (!s) return nullptr;
+  const Block* b = s->find(layer);
+  return b ? (void*)(s->slab + b->off) : nullptr;
+}
+
+ls_status ls_stage_load_block(ls_stage* s, const void* host_ptr, int layer, void* hip_stream) {
+  if (!s || !host_ptr) return fail(LS_ERR_INVALID_ARG, "ls_stage_load_block: NULL argument");
+  Block* b = s->find(layer);
+  if (!b) return fail(LS_ERR_BLOCK_RANGE, "ls_stage_load_block: block %d is not held by stage [%d,%d)", layer, s->lo, s->hi);
+  if (b->state != NOT_LOADED) return fail(LS_ERR_ALREADY_LOADED, "ls_stage_load_block: block %d already enqueued", layer);
+  hipStream_t st = (hipStream_t)hip_stream;
+  b->timed = s->profiling;
+  if (s->profiling) {
+    LS_HIP(hipEventRecord(b->copy_start, st));
+    if (s->origin_block < 0) s->origin_block = (int)(b - s->blocks.data());
+  }
+  LS_HIP(hipMemcpyAsync(s->slab + b->off, host_ptr, b->bytes, hipMemcpyHostToDevice, st));
+  LS_HIP(hipEventRecord(b->loaded, st));
+  b->state = ENQUEUED;
+  return LS_OK;
+}
+
+ls_status ls_stage_adopt_block(ls_stage* s, int layer, void* hip_stream) {
+  if (!s) return fail(LS_ERR_INVALID_ARG, "ls_stage_adopt_block: NULL stage");
+  Block* b = s->find(layer);
+  if (!b) return fail(LS_ERR_BLOCK_RANGE, "ls_stage_adopt_block: block %d is not held by stage [%d,%d)", layer, s->lo, s->hi);
+  if (b->state != NOT_LOADED) return fail(LS_ERR_ALREADY_LOADED, "ls_stage_adopt_block: block %d already enqueued", layer);
+  b->timed = false;
+  LS_HIP(hipEventRecord(b->loaded, (hipStream_t)hip_stream));
+  b->state = ENQUEUED;
+  return LS_OK;
+}
+
+ls_status ls_stage_reset_blocks(ls_stage* s) {
+  if (!s) return fail(LS_ERR_INVALID_ARG, "ls_stage_reset_blocks: NULL stage");
+  for (auto& b : s->blocks) {
+    b.state = NOT_LOADED;
+    b.timed = false;
+  }
+  s->origin_block = -1;
+  return LS_OK;
+}
+
+ls_status ls_stage_set_profiling(ls_stage* s, int on) {
+  if (!s) return fail(LS_ERR_INVALID_ARG, "ls_stage_set_profiling: NULL stage");
+  s->profiling = on != 0;
+  if (!on) s->compute_timed = false;
+  return LS_OK;
+}
+
+}  // extern "C"
+
+// ---- the forward pass -------------------------------------------------------------------
+namespace {
+
+ls_status forward(ls_stage* s, bool prefill, const void* in, const int32_t* cu_dev, int batch, int rows,
+                  const ls_kv* kv, void* out, float* logits_out, hipStream_t st) {
+  using namespace ls;
+  const ls_cfg& c = s->cfg;
+  const uint32_t dt = c.dtype;
+  const int d = c.hidden, hq = c.n_q_heads, hkv = c.n_kv_heads, hd = c.head_dim, F = c.ffn;
+  const int qkv_cols = (hq + 2 * hkv) * hd;
+  const size_t e = isz(&c);
+  char* ws = s->ws;
+  float* x = (float*)(ws + s->w.x);
+  void* y = ws + s->w.y;
+  void* qkv = ws + s->w.qkv;
+  void* attn = ws + s->w.attn;
+  void* hbuf = ws + s->w.h;
+  const float* cs = (const float*)(ws + s->w.cs);
+  int32_t* row_seq = (int32_t*)(ws + s->w.row_seq);
+  int32_t* row_pos = (int32_t*)(ws + s->w.row_pos);
+  int32_t* last_rows = (int32_t*)(ws + s->w.last_rows);
+  const bool timed = s->profiling && prefill;
+
+  if (prefill) launch_row_index_prefill(cu_dev, batch, rows, row_seq, row_pos, last_rows, st);
+  else launch_row_index_decode(kv->seq_lens, batch, c.max_seq, row_seq, row_pos, last_rows, st);
+
+  if (s->first) {
+    const Block* eb = s->find(LS_BLOCK_EMBED);
+    LS_HIP(hipStreamWaitEvent(st, eb->loaded, 0));  // gate: embedding block has landed
+    launch_embed(dt, s->slab + eb->off, (const int32_t*)in, x, rows, d, c.vocab, st);
+  } else {
+    launch_load_hidden(dt, in, x, (size_t)rows * d, st);
+  }
+
+  const size_t kv_layer = (size_t)c.max_batch * hkv * c.max_seq * hd * e;
+  for (int li = 0; li < s->hi - s->lo; ++li) {
+    const Block& b = s->blocks[s->layer0 + li];
+    TensorSpan sp[6];
+    block_tensors(&c, b.layer, sp, nullptr);
+    const char* base = s->slab + b.off;
+    // the gate: nothing of this layer may read its weights before its block has landed
+    LS_HIP(hipStreamWaitEvent(st, b.loaded, 0));
+    if (timed) LS_HIP(hipEventRecord(s->comp_start[li], st));
+    char* kc = (char*)kv->k + li * kv_layer;
+    char* vc = (char*)kv->v + li * kv_layer;
+
+    launch_rmsnorm(dt, x, base + sp[0].off, y, rows, d, c.rms_eps, nullptr, st);
+    launch_gemm(dt, EPI_STORE, y, base + sp[1].off, rows, qkv_cols, d, qkv, nullptr, st);
+    launch_rope_append(dt, qkv, cs, row_seq, row_pos, rows, hq, hkv, hd, c.max_seq, kc, vc, st);
+    launch_attention(dt, qkv, qkv_cols, kc, vc, row_seq, row_pos, rows, hq, hkv, hd, c.max_seq, attn, st);
+    launch_gemm(dt, EPI_RESID, attn, base + sp[2].off, rows, d, hq * hd, nullptr, x, st);
+    launch_rmsnorm(dt, x, base + sp[3].off, y, rows, d, c.rms_eps, nullptr, st);
+    launch_gemm(dt, EPI_SWIGLU, y, base + sp[4].off, rows, F, d, hbuf, nullptr, st);
+    launch_gemm(dt, EPI_RESID, hbuf, base + sp[5].off, rows, d, F, nullptr, x, st);
+    if (timed) LS_HIP(hipEventRecord(s->comp_end[li], st));
+  }
+  if (timed) s->compute_timed = true;
+
+  if (s->last) {
+    const Block* hb = s->find(s->hi);
+    TensorSpan sp[6];
+    block_tensors(&c, hb->layer, sp, nullptr);
+    const char* base = s->slab + hb->off;
+    LS_HIP(hipStreamWaitEvent(st, hb->loaded, 0));  // gate: head block has landed
+    float* logits = logits_out ? logits_out : (float*)(ws + s->w.logits);
+    launch_rmsnorm(dt, x, base + sp[0].off, y, batch, d, c.rms_eps, last_rows, st);
+    launch_gemm(dt, EPI_F32, y, base + sp[1].off, batch, c.vocab, d, logits, nullptr, st);
+    launch_argmax(logits, batch, c.vocab, (int32_t*)out, st);
+  } else {
+    launch_store_hidden(dt, x, out, (size_t)rows * d, st);
+  }
+
+  if (prefill) launch_seq_lens_set(cu_dev, batch, kv->seq_lens, st);
+  else launch_seq_lens_inc(batch, c.max_seq, kv->seq_lens, st);
+  LS_HIP(hipGetLastError());
+  return LS_OK;
+}
+
+ls_status common_checks(const char* who, ls_stage* s, const void* in, int batch, const ls_kv* kv, void* out,
+                        float* logits_out) {
+  if (!s || !in || !kv || !out) return fail(LS_ERR_INVALID_ARG, "%s: NULL argument", who);
+  if (!kv->k || !kv->v || !kv->seq_lens) return fail(LS_ERR_INVALID_ARG, "%s: NULL pointer inside ls_kv", who);
+  if (batch < 1 || batch > (int)s->cfg.max_batch)
+    return fail(LS_ERR_INVALID_ARG, "%s: batch %d outside [1,%u]", who, batch, s->cfg.max_batch);
+  if (logits_out && !s->last) return fail(LS_ERR_INVALID_ARG, "%s: logits_out given but the stage has no LM head", who);
+  for (const auto& b : s->blocks)
+    if (b.state == NOT_LOADED) return fail(LS_ERR_NOT_LOADED, "%s: block %d has not been enqueued for load", who, b.layer);
+  return LS_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+ls_status ls_stage_prefill(ls_stage* s, const void* in, const int32_t* cu_dev, const int32_t* cu_host, int batch,
+                           int total_tokens, const ls_kv* kv, void* out, float* logits_out, void* hip_stream) {
+  ls_status rc = common_checks("ls_stage_prefill", s, in, batch, kv, out, logits_out);
+  if (rc != LS_OK) return rc;
+  if (!cu_dev || !cu_host) return fail(LS_ERR_INVALID_ARG, "ls_stage_prefill: NULL cu_seqlens");
+  if (total_tokens < batch || total_tokens > (int)s->cfg.max_tokens)
+    return fail(LS_ERR_INVALID_ARG, "ls_stage_prefill: total_tokens %d outside [%d,%u]", total_tokens, batch, s->cfg.max_tokens);
+  if (cu_host[0] != 0 || cu_host[batch] != total_tokens)
+    return fail(LS_ERR_INVALID_ARG, "ls_stage_prefill: cu_seqlens must start at 0 and end at total_tokens");
+  for (int b = 0; b < batch; ++b) {
+    int len = cu_host[b + 1] - cu_host[b];
+    if (len < 1) return fail(LS_ERR_INVALID_ARG, "ls_stage_prefill: sequence %d has length %d", b, len);
+    if (len > (int)s->cfg.max_seq)
+      return fail(LS_ERR_KV_OVERFLOW, "ls_stage_prefill: sequence %d has %d tokens, max_seq is %u", b, len, s->cfg.max_seq);
+  }
+  return forward(s, true, in, cu_dev, batch, total_tokens, kv, out, logits_out, (hipStream_t)hip_stream);
+}
+
+ls_status ls_stage_decode(ls_stage* s, const void* in, int batch, int max_ctx, const ls_kv* kv, void* out,
+                          float* logits_out, void* hip_stream) {
+  ls_status rc = common_checks("ls_stage_decode", s, in, batch, kv, out, logits_out);
+  if (rc != LS_OK) return rc;
+  if (max_ctx < 0) return fail(LS_ERR_INVALID_ARG, "ls_stage_decode: max_ctx %d is negative", max_ctx);
+  if (max_ctx + 1 > (int)s->cfg.max_seq)
+    return fail(LS_ERR_KV_OVERFLOW, "ls_stage_decode: context %d + 1 exceeds max_seq %u", max_ctx, s->cfg.max_seq);
+  return forward(s, false, in, nullptr, batch, batch, kv, out, logits_out, (hipStream_t)hip_stream);
+}
+
+ls_status ls_stage_layer_times(ls_stage* s, float* copy_ms, float* compute_ms, float* copy_end_ms,
+                               float* compute_end_ms, int n) {
+  if (!s || n < 0 || n > s->hi - s->lo) return fail(LS_ERR_INVALID_ARG, "ls_stage_layer_times: bad arguments");
+  const bool want_copy = copy_ms || copy_end_ms, want_comp = compute_ms || compute_end_ms;
+  if (want_comp && !s->compute_timed)
+    return fail(LS_ERR_INVALID_ARG, "ls_stage_layer_times: no prefill was recorded with profiling on");
+  hipEvent_t origin = s->origin_block >= 0 ? s->blocks[s->origin_block].copy_start
+                                           : (s->compute_timed ? s->comp_start[0] : nullptr);
+  for (int i = 0; i < n; ++i) {
+    const Block& b = s->blocks[s->layer0 + i];
+    if (want_copy) {
+      if (!b.timed) return fail(LS_ERR_INVALID_ARG, "ls_stage_layer_times: block %d was not copied with profiling on", b.layer);
+      if (copy_ms) LS_HIP(hipEventElapsedTime(&copy_ms[i], b.copy_start, b.loaded));
+      if (copy_end_ms) LS_HIP(hipEventElapsedTime(&copy_end_ms[i], origin, b.loaded));
+    }
+    if (compute_ms) LS_HIP(hipEventElapsedTime(&compute_ms[i], s->comp_start[i], s->comp_end[i]));
+    if (compute_end_ms) LS_HIP(hipEventElapsedTime(&compute_end_ms[i], origin, s->comp_end[i]));
+  }
+  return LS_OK;
+}
+
+}  // extern "C"
