@@ -12,6 +12,10 @@ import os
 from typing import Dict, Optional, Sequence
 
 import numpy as np
+# PyTorch ships its own HIP runtime (same SONAME as ROCm's).  It must be in the process
+# before libls_stage.so is opened, so that the library binds to that one runtime and its
+# streams, events and device pointers mean the same thing on both sides.
+import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libls_stage.so")
@@ -115,8 +119,6 @@ class Stage:
     """One ls_stage plus the device buffers it needs, allocated with PyTorch."""
 
     def __init__(self, shape, layer_lo: int, layer_hi: int, max_batch: int, max_seq: int, max_tokens: int, device="cuda:0"):
-        import torch
-
         self.torch = torch
         self.shape, self.lo, self.hi = shape, layer_lo, layer_hi
         self.cfg = make_cfg(shape, max_batch, max_seq, max_tokens)
