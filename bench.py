@@ -1,0 +1,230 @@
+"""Benchmark of the stage hot path on one MI355X.
+
+One step = one pass of the whole hot path over one batch: the prompt pass of the stage
+followed by the KV-cached decode steps of the workload.  Default workload: the
+Llama-7B-shaped middle stage (layers 8..15 of 32, bf16), batch 8 x 512 prompt tokens of
+N(0,1) hidden states, then 128 decode steps.  Weights are seeded synthetic N(0, 0.02)
+(gains 1 + N(0, 0.02)), packed per layer, copied from pinned host memory by the library's
+loader and resident in HBM before the timed region starts.
+
+Prints ONE JSON line (see the keys below).  `value` is tokens handled per second over the
+whole step (prompt tokens + generated tokens, divided by prefill + decode time).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+from concurrent.futures import ThreadPoolExecutor
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0      # MI355X published HBM3E bandwidth
+MFMA_BF16_PEAK_TF = 2500.0  # MI355X published dense bf16 MFMA rate
+
+WORKLOADS = {
+    # name: (shape key, layer_lo, layer_hi, batch, prompt, decode steps)
+    "llama7b_stage_l8_16_b8_s512_d128": ("llama7b", 8, 16, 8, 512, 128),
+    "tiny_f32_b1_s32_d8": ("tiny_f32", 0, 2, 1, 32, 8),
+}
+SEED = 1234
+
+
+def build_stage(synth, Stage, pack_block, shape, lo, hi, batch, prompt, steps):
+    import torch
+
+    st = Stage(shape, lo, hi, batch, prompt + steps, batch * prompt)
+
+    def make(layer):
+        if layer == -1:
+            t, order = synth.embed_tensors(shape, SEED), ("embed",)
+        elif layer == shape.n_layers_total:
+            t, order = synth.head_tensors(shape, SEED), synth.TENSOR_ORDER_HEAD
+        else:
+            t, order = synth.layer_tensors(shape, SEED, layer), synth.TENSOR_ORDER_LAYER
+        host = torch.empty(int(st_block_bytes(st, layer)), dtype=torch.uint8, pin_memory=True)
+        pack_block(st.cfg, layer, [t[n] for n in order], out=host.numpy())
+        return layer, host
+
+    with ThreadPoolExecutor(max_workers=8) as ex:
+        blocks = dict(ex.map(make, st.block_ids()))
+    return st, blocks
+
+
+def st_block_bytes(st, layer):
+    from paper_2502_09922_amd import binding as b
+
+    return b.ls_stage_block_bytes(st.handle, layer)
+
+
+def cpu_baseline(synth, shape, lo, batch):
+    """The oracle as it stands, timed on this machine's host cores on a bounded sample of the
+    same workload: ONE layer at the real dimensions, `batch` sequences of 64 prompt tokens
+    and 2 decode steps; scaled linearly in layers to the stage (extrapolated)."""
+    from oracle.stage_oracle import OracleStage
+
+    import threadpoolctl
+
+    n_prompt, n_dec = 64, 2
+    one = shape.with_(vocab=0)
+    ora = OracleStage(one, lo, lo + 1, batch, n_prompt + n_dec)
+    ora.load_tensors(lo, synth.layer_tensors(one, SEED, lo))
+    x = synth.hidden_states(one, SEED + 1, batch * n_prompt)
+    t0 = time.perf_counter()
+    ora.prefill(x, [n_prompt] * batch)
+    for t in range(n_dec):
+        ora.decode(synth.hidden_states(one, SEED + 2 + t, batch))
+    dt = time.perf_counter() - t0
+    threads = max([p["num_threads"] for p in threadpoolctl.threadpool_info()] or [1])
+    return dt, batch * (n_prompt + n_dec), threads, n_prompt, n_dec
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="llama7b_stage_l8_16_b8_s512_d128", choices=sorted(WORKLOADS))
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1")
+
+    import torch
+
+    import synth
+    from paper_2502_09922_amd import Stage, pack_block, binding as B
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    key, lo, hi, batch, prompt, dsteps = WORKLOADS[args.workload]
+    shape = synth.CONFIGS[key]
+    t_gen = time.perf_counter()
+    st, blocks = build_stage(synth, Stage, pack_block, shape, lo, hi, batch, prompt, dsteps)
+    t_gen = time.perf_counter() - t_gen
+    stream = torch.cuda.current_stream()
+    for layer in st.block_ids():
+        st.load_block(layer, blocks[layer], stream=stream)
+    torch.cuda.synchronize()
+
+    T = batch * prompt
+    if st.first:
+        x_prefill = torch.from_numpy(synth.token_ids(SEED + 1, T, shape.vocab)).cuda()
+        x_decode = [torch.from_numpy(synth.token_ids(SEED + 2 + t, batch, shape.vocab)).cuda() for t in range(dsteps)]
+    else:
+        def dev(a):
+            if a.dtype == np.uint16:
+                return torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16)
+            return torch.from_numpy(a).cuda()
+        x_prefill = dev(synth.hidden_states(shape, SEED + 1, T))
+        x_decode = [dev(synth.hidden_states(shape, SEED + 2 + t, batch)) for t in range(dsteps)]
+    out_dec = (torch.empty(batch, dtype=torch.int32, device="cuda") if st.last
+               else torch.empty(batch, shape.hidden, dtype=st.tdtype, device="cuda"))
+    lengths = [prompt] * batch
+
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+    mid_layer = (lo + hi) // 2
+
+    def one_step(timed):
+        if timed:
+            ev[0].record(stream)
+        st.prefill(x_prefill, lengths)
+        if timed:
+            ev[1].record(stream)
+        for t in range(dsteps):
+            st.decode(x_decode[t], batch, prompt + t, out=out_dec)
+        if timed:
+            ev[2].record(stream)
+
+    for _ in range(args.warmup):
+        one_step(False)
+    torch.cuda.synchronize()
+
+    # probe the decode gate-up GEMM (the kernel that moves the most bytes) of one layer
+    st.probe(B.LS_OP_GEMM_GATEUP, mid_layer, 1)
+    t_pre = t_dec = 0.0
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        one_step(True)
+        torch.cuda.synchronize()
+        t_pre += ev[0].elapsed_time(ev[1])
+        t_dec += ev[1].elapsed_time(ev[2])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    probe_dec = st.probe_times()
+    st.probe(B.LS_OP_NONE)
+
+    # one more (untimed) prompt pass with the probe on the prefill gate-up GEMM
+    st.probe(B.LS_OP_GEMM_GATEUP, mid_layer, 0)
+    st.prefill(x_prefill, lengths)
+    st.prefill(x_prefill, lengths)
+    torch.cuda.synchronize()
+    probe_pre = st.probe_times()
+    st.probe(B.LS_OP_NONE)
+
+    ms_step = wall * 1e3 / args.steps
+    t_pre /= args.steps
+    t_dec /= args.steps
+    tokens = T + batch * dsteps
+    d, F, e = shape.hidden, shape.ffn, shape.itemsize
+    # decode gate-up GEMM: algorithmic bytes = the two stacked projections read once, plus
+    # the activations in and out
+    gu_bytes = 2 * F * d * e + batch * d * e + batch * F * e
+    gu_ms = float(np.mean(probe_dec)) if probe_dec else float("nan")
+    achieved = gu_bytes / (gu_ms * 1e-3) / 1e9
+    # prefill gate-up GEMM: 2 * T * 2F * d flops
+    pg_flops = 2.0 * T * 2 * F * d
+    pg_ms = float(np.mean(probe_pre)) if probe_pre else float("nan")
+    pg_tf = pg_flops / (pg_ms * 1e-3) / 1e12
+
+    # whole-phase algorithmic work
+    L = hi - lo
+    wbytes = sum(st_block_bytes(st, l) for l in range(lo, hi))
+    kv_tok = 2 * shape.n_kv_heads * shape.head_dim * e
+    dec_bytes = sum(wbytes + batch * (prompt + t + 1) * kv_tok * L for t in range(dsteps))
+    p_mm = (shape.qkv_rows * d + d * shape.n_q_heads * shape.head_dim + 3 * F * d)
+    pre_flops = 2.0 * T * p_mm * L + 2.0 * shape.n_q_heads * shape.head_dim * prompt * (prompt + 1) * batch * L
+
+    res = {
+        "metric": "stage prefill+decode tokens/s (1 GPU)",
+        "value": tokens / (ms_step * 1e-3),
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32" if shape.dtype == "f32" else "bf16",
+        "data": "synthetic",
+        "config": {"workload": args.workload, "layers": [lo, hi], "batch": batch, "prompt": prompt,
+                   "decode_steps": dsteps, "weights_gen_s": round(t_gen, 1)},
+        "prefill": {"ms": t_pre, "tokens_per_s": T / (t_pre * 1e-3), "tflops": pre_flops / (t_pre * 1e-3) / 1e12,
+                    "frac_of_bf16_mfma_peak": pre_flops / (t_pre * 1e-3) / 1e12 / MFMA_BF16_PEAK_TF},
+        "decode": {"ms": t_dec, "ms_per_token_step": t_dec / dsteps, "tokens_per_s": batch * dsteps / (t_dec * 1e-3),
+                   "gbytes_per_s": dec_bytes / (t_dec * 1e-3) / 1e9,
+                   "frac_of_hbm_peak": dec_bytes / (t_dec * 1e-3) / 1e9 / HBM_PEAK_GBS},
+        "roofline": {"kernel": "decode gate-up GEMM + SwiGLU", "bound": "hbm", "achieved": achieved,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "bytes_per_launch": gu_bytes, "avg_ms": gu_ms, "launches_timed": len(probe_dec)},
+        "roofline_prefill": {"kernel": "prefill gate-up GEMM + SwiGLU", "bound": "mfma", "achieved": pg_tf,
+                             "peak": MFMA_BF16_PEAK_TF, "unit": "TFLOP/s", "frac": pg_tf / MFMA_BF16_PEAK_TF,
+                             "flops_per_launch": pg_flops, "avg_ms": pg_ms, "launches_timed": len(probe_pre)},
+    }
+    if not args.no_cpu_baseline:
+        dt, ntok, threads, n_prompt, n_dec = cpu_baseline(synth, shape, lo, batch)
+        res["cpu_baseline"] = {
+            "value": ntok / (dt * L), "unit": "tokens/s", "cores": threads, "kind": "oracle",
+            "sample": "1 of %d layers at real dims, %d seqs x (%d prompt + %d decode) tokens in %.1f s; "
+                      "scaled linearly to %d layers (extrapolated)" % (L, batch, n_prompt, n_dec, dt, L),
+        }
+    st.close()
+    print(json.dumps(res))
+
+
+if __name__ == "__main__":
+    main()

@@ -220,6 +220,28 @@ ls_status ls_stage_set_profiling(ls_stage* stage, int on);
 ls_status ls_stage_layer_times(ls_stage* stage, float* copy_ms, float* compute_ms,
                                float* copy_end_ms, float* compute_end_ms, int n);
 
+/* Operators of one decoder layer that ls_stage_probe can time. */
+#define LS_OP_NONE 0
+#define LS_OP_NORM 1        /* attention RMSNorm                    */
+#define LS_OP_GEMM_QKV 2    /* y Wqkv^T                             */
+#define LS_OP_ROPE 3        /* RoPE + KV append                     */
+#define LS_OP_ATTENTION 4   /* causal attention                     */
+#define LS_OP_GEMM_O 5      /* x += o Wo^T                          */
+#define LS_OP_GEMM_GATEUP 6 /* silu(y Wg^T) * (y Wu^T)              */
+#define LS_OP_GEMM_DOWN 7   /* x += h Wd^T                          */
+
+/*
+ * Bracket every launch of operator `op` in decoder layer `layer` with a HIP event pair on
+ * the call's own stream, in prefill calls (phase 0) or decode calls (phase 1); op
+ * LS_OP_NONE switches the probe off.  The last 512 launches are kept.  Used to measure one
+ * kernel's duration inside a timed run without a profiler attached.
+ */
+ls_status ls_stage_probe(ls_stage* stage, int op, int layer, int phase);
+
+/* After the caller has synchronised: durations in ms of the probed launches since the
+ * probe was set, oldest first, at most `cap`; *n receives the count. */
+ls_status ls_stage_probe_times(ls_stage* stage, float* ms, int cap, int* n);
+
 /* Message of the last failing call on this thread ("" if none). */
 const char* ls_last_error(void);
 

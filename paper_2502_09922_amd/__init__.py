@@ -1,7 +1,17 @@
 """MI355X-native execute-while-load pipeline-stage executor (HIP kernels + C ABI).
 
 `binding` loads libls_stage.so and exposes the entry points of include/ls_stage.h
-under the same names; `build` compiles the library in-tree for gfx950.
+under the same names; `build` compiles the library in-tree for gfx950.  The binding is
+imported on first use, so that `python -m paper_2502_09922_amd.build` can run before the
+library exists; a missing library is an ImportError, never a fallback.
 """
-from . import binding  # noqa: F401  (raises ImportError if the library is not built)
-from .binding import Stage, LsError, ls_cfg, ls_kv, make_cfg, pack_block  # noqa: F401
+_LAZY = ("binding", "Stage", "LsError", "ls_cfg", "ls_kv", "make_cfg", "pack_block")
+
+
+def __getattr__(name):
+    if name in _LAZY:
+        import importlib
+
+        binding = importlib.import_module(".binding", __name__)
+        return binding if name == "binding" else getattr(binding, name)
+    raise AttributeError(name)

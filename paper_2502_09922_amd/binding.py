@@ -30,6 +30,8 @@ lib = C.CDLL(LIB_PATH)
 LS_ABI_VERSION = 1
 LS_DTYPE_F32, LS_DTYPE_BF16 = 0, 1
 LS_BLOCK_EMBED = -1
+(LS_OP_NONE, LS_OP_NORM, LS_OP_GEMM_QKV, LS_OP_ROPE, LS_OP_ATTENTION, LS_OP_GEMM_O,
+ LS_OP_GEMM_GATEUP, LS_OP_GEMM_DOWN) = range(8)
 (LS_OK, LS_ERR_INVALID_ARG, LS_ERR_BLOCK_RANGE, LS_ERR_NOT_LOADED, LS_ERR_ALREADY_LOADED,
  LS_ERR_KV_OVERFLOW, LS_ERR_OOM, LS_ERR_HIP) = (0, -1, -2, -3, -4, -5, -6, -7)
 
@@ -67,6 +69,8 @@ _SIGS = {
     "ls_stage_decode": (C.c_int, [_P, _P, C.c_int, C.c_int, C.POINTER(ls_kv), _P, _P, _P]),
     "ls_stage_set_profiling": (C.c_int, [_P, C.c_int]),
     "ls_stage_layer_times": (C.c_int, [_P, C.POINTER(C.c_float), C.POINTER(C.c_float), C.POINTER(C.c_float), C.POINTER(C.c_float), C.c_int]),
+    "ls_stage_probe": (C.c_int, [_P, C.c_int, C.c_int, C.c_int]),
+    "ls_stage_probe_times": (C.c_int, [_P, C.POINTER(C.c_float), C.c_int, C.POINTER(C.c_int)]),
     "ls_last_error": (C.c_char_p, []),
 }
 for _name, (_res, _args) in _SIGS.items():
@@ -211,6 +215,14 @@ class Stage:
             self.handle, inp.data_ptr(), batch, max_ctx, C.byref(self.kv), out.data_ptr(),
             logits.data_ptr() if logits is not None else None, self._stream_ptr(stream)))
         return (out, logits) if want_logits else out
+
+    def probe(self, op: int, layer: int = 0, phase: int = 1):
+        check(lib.ls_stage_probe(self.handle, op, layer, phase))
+
+    def probe_times(self):
+        arr, n = (C.c_float * 512)(), C.c_int()
+        check(lib.ls_stage_probe_times(self.handle, arr, 512, C.byref(n)))
+        return list(arr[: n.value])
 
     def set_profiling(self, on: bool):
         check(lib.ls_stage_set_profiling(self.handle, int(on)))

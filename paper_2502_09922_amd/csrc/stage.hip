@@ -112,6 +112,7 @@ Carve carve(const ls_cfg* c, int lo, int hi) {
 }
 
 enum BlockState { NOT_LOADED = 0, ENQUEUED = 1 };
+constexpr int PROBE_CAP = 512;
 
 struct Block {
   int layer;
@@ -136,6 +137,10 @@ struct ls_stage {
   bool compute_timed;
   int origin_block;  // first block copied with profiling on since the last reset, or -1
   std::vector<hipEvent_t> comp_start, comp_end;
+  // kernel probe: event pairs around one operator of one layer, a ring of PROBE_CAP pairs
+  int probe_op, probe_layer, probe_phase;
+  size_t probe_count;
+  std::vector<hipEvent_t> probe_a, probe_b;
 
   Block* find(int layer) {
     for (auto& b : blocks)
@@ -210,6 +215,9 @@ ls_status ls_stage_create(const ls_cfg* cfg, int lo, int hi, void* weight_slab, 
   s->profiling = false;
   s->compute_timed = false;
   s->origin_block = -1;
+  s->probe_op = LS_OP_NONE;
+  s->probe_layer = s->probe_phase = 0;
+  s->probe_count = 0;
 
   size_t off = 0;
   auto add = [&](int layer) {
@@ -233,6 +241,8 @@ ls_status ls_stage_create(const ls_cfg* cfg, int lo, int hi, void* weight_slab, 
     }
     for (auto e : s->comp_start) (void)hipEventDestroy(e);
     for (auto e : s->comp_end) (void)hipEventDestroy(e);
+    for (auto e : s->probe_a) (void)hipEventDestroy(e);
+    for (auto e : s->probe_b) (void)hipEventDestroy(e);
     delete s;
   };
   for (auto& b : s->blocks) {
@@ -278,6 +288,8 @@ void ls_stage_destroy(ls_stage* s) {
   }
   for (auto e : s->comp_start) (void)hipEventDestroy(e);
   for (auto e : s->comp_end) (void)hipEventDestroy(e);
+  for (auto e : s->probe_a) (void)hipEventDestroy(e);
+  for (auto e : s->probe_b) (void)hipEventDestroy(e);
   delete s;
 }
 
@@ -362,6 +374,19 @@ ls_status forward(ls_stage* s, bool prefill, const void* in, const int32_t* cu_d
   int32_t* row_pos = (int32_t*)(ws + s->w.row_pos);
   int32_t* last_rows = (int32_t*)(ws + s->w.last_rows);
   const bool timed = s->profiling && prefill;
+  const bool probing = s->probe_op != LS_OP_NONE && s->probe_phase == (prefill ? 0 : 1) && !s->probe_a.empty();
+  // PROBE(op, launch): bracket the launch with an event pair if this (op, layer) is probed
+#define PROBE(op, launch)                                                        \
+  do {                                                                           \
+    const bool on_ = probing && s->probe_op == (op) && s->probe_layer == b.layer; \
+    const size_t slot_ = s->probe_count % PROBE_CAP;                             \
+    if (on_) LS_HIP(hipEventRecord(s->probe_a[slot_], st));                      \
+    launch;                                                                      \
+    if (on_) {                                                                   \
+      LS_HIP(hipEventRecord(s->probe_b[slot_], st));                             \
+      s->probe_count++;                                                          \
+    }                                                                            \
+  } while (0)
 
   if (prefill) launch_row_index_prefill(cu_dev, batch, rows, row_seq, row_pos, last_rows, st);
   else launch_row_index_decode(kv->seq_lens, batch, c.max_seq, row_seq, row_pos, last_rows, st);
@@ -386,16 +411,18 @@ ls_status forward(ls_stage* s, bool prefill, const void* in, const int32_t* cu_d
     char* kc = (char*)kv->k + li * kv_layer;
     char* vc = (char*)kv->v + li * kv_layer;
 
-    launch_rmsnorm(dt, x, base + sp[0].off, y, rows, d, c.rms_eps, nullptr, st);
-    launch_gemm(dt, EPI_STORE, y, base + sp[1].off, rows, qkv_cols, d, qkv, nullptr, st);
-    launch_rope_append(dt, qkv, cs, row_seq, row_pos, rows, hq, hkv, hd, c.max_seq, kc, vc, st);
-    launch_attention(dt, qkv, qkv_cols, kc, vc, row_seq, row_pos, rows, hq, hkv, hd, c.max_seq, attn, st);
-    launch_gemm(dt, EPI_RESID, attn, base + sp[2].off, rows, d, hq * hd, nullptr, x, st);
+    PROBE(LS_OP_NORM, launch_rmsnorm(dt, x, base + sp[0].off, y, rows, d, c.rms_eps, nullptr, st));
+    PROBE(LS_OP_GEMM_QKV, launch_gemm(dt, EPI_STORE, y, base + sp[1].off, rows, qkv_cols, d, qkv, nullptr, st));
+    PROBE(LS_OP_ROPE, launch_rope_append(dt, qkv, cs, row_seq, row_pos, rows, hq, hkv, hd, c.max_seq, kc, vc, st));
+    PROBE(LS_OP_ATTENTION,
+          launch_attention(dt, qkv, qkv_cols, kc, vc, row_seq, row_pos, rows, hq, hkv, hd, c.max_seq, attn, st));
+    PROBE(LS_OP_GEMM_O, launch_gemm(dt, EPI_RESID, attn, base + sp[2].off, rows, d, hq * hd, nullptr, x, st));
     launch_rmsnorm(dt, x, base + sp[3].off, y, rows, d, c.rms_eps, nullptr, st);
-    launch_gemm(dt, EPI_SWIGLU, y, base + sp[4].off, rows, F, d, hbuf, nullptr, st);
-    launch_gemm(dt, EPI_RESID, hbuf, base + sp[5].off, rows, d, F, nullptr, x, st);
+    PROBE(LS_OP_GEMM_GATEUP, launch_gemm(dt, EPI_SWIGLU, y, base + sp[4].off, rows, F, d, hbuf, nullptr, st));
+    PROBE(LS_OP_GEMM_DOWN, launch_gemm(dt, EPI_RESID, hbuf, base + sp[5].off, rows, d, F, nullptr, x, st));
     if (timed) LS_HIP(hipEventRecord(s->comp_end[li], st));
   }
+#undef PROBE
   if (timed) s->compute_timed = true;
 
   if (s->last) {
@@ -480,6 +507,39 @@ ls_status ls_stage_layer_times(ls_stage* s, float* copy_ms, float* compute_ms, f
     if (compute_ms) LS_HIP(hipEventElapsedTime(&compute_ms[i], s->comp_start[i], s->comp_end[i]));
     if (compute_end_ms) LS_HIP(hipEventElapsedTime(&compute_end_ms[i], origin, s->comp_end[i]));
   }
+  return LS_OK;
+}
+
+ls_status ls_stage_probe(ls_stage* s, int op, int layer, int phase) {
+  if (!s) return fail(LS_ERR_INVALID_ARG, "ls_stage_probe: NULL stage");
+  if (op < LS_OP_NONE || op > LS_OP_GEMM_DOWN || (phase != 0 && phase != 1))
+    return fail(LS_ERR_INVALID_ARG, "ls_stage_probe: bad operator %d or phase %d", op, phase);
+  if (op != LS_OP_NONE && (layer < s->lo || layer >= s->hi))
+    return fail(LS_ERR_BLOCK_RANGE, "ls_stage_probe: layer %d outside [%d,%d)", layer, s->lo, s->hi);
+  if (op != LS_OP_NONE && s->probe_a.empty()) {
+    for (int i = 0; i < PROBE_CAP; ++i) {
+      hipEvent_t a = nullptr, b = nullptr;
+      if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) {
+        if (a) (void)hipEventDestroy(a);
+        return fail(LS_ERR_HIP, "ls_stage_probe: hipEventCreate failed");
+      }
+      s->probe_a.push_back(a);
+      s->probe_b.push_back(b);
+    }
+  }
+  s->probe_op = op;
+  s->probe_layer = layer;
+  s->probe_phase = phase;
+  s->probe_count = 0;
+  return LS_OK;
+}
+
+ls_status ls_stage_probe_times(ls_stage* s, float* ms, int cap, int* n) {
+  if (!s || !ms || !n || cap < 0) return fail(LS_ERR_INVALID_ARG, "ls_stage_probe_times: bad arguments");
+  size_t have = s->probe_count < (size_t)PROBE_CAP ? s->probe_count : (size_t)PROBE_CAP;
+  if (have > (size_t)cap) have = (size_t)cap;
+  for (size_t i = 0; i < have; ++i) LS_HIP(hipEventElapsedTime(&ms[i], s->probe_a[i], s->probe_b[i]));
+  *n = (int)have;
   return LS_OK;
 }
 
