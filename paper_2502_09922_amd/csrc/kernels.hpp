@@ -42,6 +42,11 @@ void launch_gemm(uint32_t dt, Epilogue epi, const void* A, const void* W, int M,
 void launch_gemm_generic(uint32_t dt, Epilogue epi, const void* A, const void* W, int M, int N, int K,
                          void* out, float* resid, hipStream_t st);
 
+// bf16 MFMA kernel for many-row GEMMs (prompt pass); needs K % 64 == 0.
+bool gemm_mfma_supported(int M, int N, int K);
+void launch_gemm_mfma(Epilogue epi, const void* A, const void* W, int M, int N, int K, void* out, float* resid,
+                      hipStream_t st);
+
 // Rotate q (in place inside qkv) and k by the per-position cos/sin table, write k and v
 // into the cache at [seq][kv head][pos].  qkv is [rows, (Hq+2Hkv)*hd].
 void launch_rope_append(uint32_t dt, void* qkv, const float* cs_table, const int32_t* row_seq,
