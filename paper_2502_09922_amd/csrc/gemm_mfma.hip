@@ -69,24 +69,6 @@ k_gemm_mfma(const bf16* __restrict__ A, const bf16* __restrict__ W, int M, int N
     wp[i] = W + (size_t)wrow * K + c * 8;
   }
   uint4 ra[4], rw[4];
-  auto load_tile = [&](int k0) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      ra[i] = *reinterpret_cast<const uint4*>(ap[i] + k0);
-      rw[i] = *reinterpret_cast<const uint4*>(wp[i] + k0);
-    }
-  };
-  auto store_tile = [&](int buf) {
-    unsigned char* as = smem + buf * 2 * TILE_BYTES;
-    unsigned char* ws = as + TILE_BYTES;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      int row = r0 + 64 * i;
-      *reinterpret_cast<uint4*>(as + swz(row, c)) = ra[i];
-      *reinterpret_cast<uint4*>(ws + swz(row, c)) = rw[i];
-    }
-  };
-
   f32x16 acc[4][2];
 #pragma unroll
   for (int i = 0; i < 4; ++i)
@@ -97,32 +79,57 @@ k_gemm_mfma(const bf16* __restrict__ A, const bf16* __restrict__ W, int M, int N
 
   const int lr = lane & 31, lh = lane >> 5;
   const int KT = K / BK;
-  load_tile(0);
-  store_tile(0);
+  // LDS byte offsets of this thread's staging chunks and of its operand reads
+  int st_off[4], a_off[4][4], b_off[4][2];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) st_off[i] = swz(r0 + 64 * i, c);
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) a_off[kk][i] = swz(wm * 128 + i * 32 + lr, kk * 2 + lh);
+#pragma unroll
+    for (int j = 0; j < 2; ++j) b_off[kk][j] = TILE_BYTES + swz(wn * 64 + j * 32 + lr, kk * 2 + lh);
+  }
+
+#define LS_LOAD_TILE(k0)                                              \
+  _Pragma("unroll") for (int i = 0; i < 4; ++i) {                     \
+    ra[i] = *reinterpret_cast<const uint4*>(ap[i] + (k0));            \
+    rw[i] = *reinterpret_cast<const uint4*>(wp[i] + (k0));            \
+  }
+#define LS_STORE_TILE(buf)                                                                   \
+  _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                            \
+    *reinterpret_cast<uint4*>(smem + (buf) * 2 * TILE_BYTES + st_off[i]) = ra[i];            \
+    *reinterpret_cast<uint4*>(smem + (buf) * 2 * TILE_BYTES + TILE_BYTES + st_off[i]) = rw[i]; \
+  }
+#define LS_COMPUTE_TILE(buf)                                                                     \
+  _Pragma("unroll") for (int kk = 0; kk < 4; ++kk) {                                             \
+    bf16x8 af[4], bfr[2];                                                                        \
+    _Pragma("unroll") for (int i = 0; i < 4; ++i)                                                \
+      af[i] = *reinterpret_cast<const bf16x8*>(smem + (buf) * 2 * TILE_BYTES + a_off[kk][i]);    \
+    _Pragma("unroll") for (int j = 0; j < 2; ++j)                                                \
+      bfr[j] = *reinterpret_cast<const bf16x8*>(smem + (buf) * 2 * TILE_BYTES + b_off[kk][j]);   \
+    _Pragma("unroll") for (int i = 0; i < 4; ++i)                                                \
+      _Pragma("unroll") for (int j = 0; j < 2; ++j)                                              \
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);  \
+  }
+
+  LS_LOAD_TILE(0)
+  LS_STORE_TILE(0)
   __syncthreads();
-  for (int kt = 0; kt < KT; ++kt) {
-    if (kt + 1 < KT) load_tile((kt + 1) * BK);
-    const unsigned char* as = smem + (kt & 1) * 2 * TILE_BYTES;
-    const unsigned char* ws = as + TILE_BYTES;
-#pragma unroll
-    for (int kk = 0; kk < 4; ++kk) {
-      const int chunk = kk * 2 + lh;
-      bf16x8 af[4], bfr[2];
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-        af[i] = *reinterpret_cast<const bf16x8*>(as + swz(wm * 128 + i * 32 + lr, chunk));
-#pragma unroll
-      for (int j = 0; j < 2; ++j)
-        bfr[j] = *reinterpret_cast<const bf16x8*>(ws + swz(wn * 64 + j * 32 + lr, chunk));
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
-    }
-    if (kt + 1 < KT) store_tile((kt + 1) & 1);
+  for (int kt = 0; kt + 1 < KT; ++kt) {
+    const int buf = kt & 1;
+    LS_LOAD_TILE((kt + 1) * BK)
+    LS_COMPUTE_TILE(buf)
+    LS_STORE_TILE(buf ^ 1)
     __syncthreads();
   }
+  {
+    const int buf = (KT - 1) & 1;
+    LS_COMPUTE_TILE(buf)
+  }
+#undef LS_LOAD_TILE
+#undef LS_STORE_TILE
+#undef LS_COMPUTE_TILE
 
   // ---- epilogue
 #pragma unroll
