@@ -23,7 +23,12 @@ constexpr int TILE_BYTES = BM * BK * 2;         // 32 KB per operand tile
 constexpr int SMEM_BYTES = 4 * TILE_BYTES;      // A and W, two buffers each
 constexpr int GROUP_M = 4;
 
-__device__ __forceinline__ int swz(int row, int chunk) { return row * 128 + ((chunk ^ (row & 7)) << 4); }
+#ifndef LS_GEMM_SWZ_SHIFT
+#define LS_GEMM_SWZ_SHIFT 1
+#endif
+__device__ __forceinline__ int swz(int row, int chunk) {
+  return row * 128 + ((chunk ^ ((row >> LS_GEMM_SWZ_SHIFT) & 7)) << 4);
+}
 
 template <int EPI>
 __global__ void __launch_bounds__(512, 1)
