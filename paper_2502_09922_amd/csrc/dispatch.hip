@@ -6,6 +6,10 @@ namespace ls {
 
 void launch_gemm(uint32_t dt, Epilogue epi, const void* A, const void* W, int M, int N, int K, void* out,
                  float* resid, hipStream_t st) {
+  if (dt == BF16 && gemm_skinny_supported(M, N, K)) {
+    launch_gemm_skinny(epi, A, W, M, N, K, out, resid, 0, st);
+    return;
+  }
   if (dt == BF16 && M > 64 && gemm_mfma_supported(M, N, K)) {
     launch_gemm_mfma(epi, A, W, M, N, K, out, resid, st);
     return;

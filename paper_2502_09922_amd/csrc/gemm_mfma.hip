@@ -73,7 +73,7 @@ k_gemm_mfma(const bf16* __restrict__ A, const bf16* __restrict__ W, int M, int N
     }
     wp[i] = W + (size_t)wrow * K + c * 8;
   }
-  uint4 ra[4], rw[4];
+  u32x4 ra[4], rw[4];
   f32x16 acc[4][2];
 #pragma unroll
   for (int i = 0; i < 4; ++i)
@@ -98,13 +98,13 @@ k_gemm_mfma(const bf16* __restrict__ A, const bf16* __restrict__ W, int M, int N
 
 #define LS_LOAD_TILE(k0)                                              \
   _Pragma("unroll") for (int i = 0; i < 4; ++i) {                     \
-    ra[i] = *reinterpret_cast<const uint4*>(ap[i] + (k0));            \
-    rw[i] = *reinterpret_cast<const uint4*>(wp[i] + (k0));            \
+    ra[i] = *reinterpret_cast<const u32x4*>(ap[i] + (k0));            \
+    rw[i] = *reinterpret_cast<const u32x4*>(wp[i] + (k0));            \
   }
 #define LS_STORE_TILE(buf)                                                                   \
   _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                            \
-    *reinterpret_cast<uint4*>(smem + (buf) * 2 * TILE_BYTES + st_off[i]) = ra[i];            \
-    *reinterpret_cast<uint4*>(smem + (buf) * 2 * TILE_BYTES + TILE_BYTES + st_off[i]) = rw[i]; \
+    *reinterpret_cast<u32x4*>(smem + (buf) * 2 * TILE_BYTES + st_off[i]) = ra[i];            \
+    *reinterpret_cast<u32x4*>(smem + (buf) * 2 * TILE_BYTES + TILE_BYTES + st_off[i]) = rw[i]; \
   }
 #define LS_COMPUTE_TILE(buf)                                                                     \
   _Pragma("unroll") for (int kk = 0; kk < 4; ++kk) {                                             \

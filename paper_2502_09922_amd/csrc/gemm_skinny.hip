@@ -1,0 +1,193 @@
+// bf16 weight-streaming GEMM for decode steps: C[M,N] = X[M,K] W[N,K]^T with M <= 64.
+//
+// At M <= 64 every weight byte is used for at most 64 multiply-adds, so the kernel is bound
+// by how fast W streams out of HBM (roofline: HBM bandwidth), and the design goal is to read
+// each byte of W exactly once with fully used cache lines and many bytes in flight.
+//
+//   * A workgroup owns 16 output columns (16 rows of W; with the SwiGLU epilogue, the 16
+//     gate rows and the 16 up rows of the same columns).  Its KS wavefronts split K.
+//   * A wavefront walks its K range in blocks of 128: four 16-byte-per-lane global loads
+//     fetch 16 rows x 256 contiguous bytes (a quarter-wave per row, whole cache lines), held
+//     in a register ring several blocks deep so that >= 8 KB per wave is always in flight.
+//   * Each block passes through a wave-private 4 KB LDS scratch (written lane-linear, chunks
+//     XOR-swizzled by row) to reach the MFMA operand layout: v_mfma_f32_16x16x32_bf16 with
+//     W as the A operand (row = lane%16, 8 k-values per lane) and X as the B operand
+//     (column m = lane%16); a lane of the result holds m = lane%16, n = 4*(lane/16) + r.
+//   * The KS partial tiles are summed through LDS in wave order (fixed order: results are
+//     reproducible), then the epilogue stores, adds to the residual stream, or applies SwiGLU.
+#include "kernels.hpp"
+#include "device_util.hpp"
+
+namespace ls {
+
+namespace {
+
+template <int MT, int EPI, int KS, int PF>
+__global__ void __launch_bounds__(KS * 64)
+k_gemm_skinny(const bf16* __restrict__ X, const bf16* __restrict__ W, int M, int N, int K,
+              void* __restrict__ outv, float* __restrict__ resid) {
+  constexpr bool GLU = (EPI == EPI_SWIGLU);
+  constexpr int NW = GLU ? 2 : 1;                      // weight streams per wave
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lr = lane & 15, lg = lane >> 4;
+  const int n0 = blockIdx.x * 16;
+  const int nblk = K >> 7;
+  const int b0 = (int)((long)wave * nblk / KS), b1 = (int)((long)(wave + 1) * nblk / KS);
+  const int nb = b1 - b0;
+  unsigned char* scratch = smem + wave * (NW * 4096);
+
+  // per-lane global offsets (elements) of the four load instructions of a block
+  size_t woff[NW][4];
+#pragma unroll
+  for (int s = 0; s < NW; ++s)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int row = 4 * i + lg;
+      woff[s][i] = (size_t)(s * N + n0 + row) * K + (size_t)((lr ^ row) << 3);
+    }
+  size_t xoff[MT];
+#pragma unroll
+  for (int t = 0; t < MT; ++t) xoff[t] = (size_t)min(lr + 16 * t, M - 1) * K + (size_t)(lg << 3);
+  int a_off[4];  // LDS byte offset of the A fragment of k-step kk
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk) a_off[kk] = lr * 256 + (((kk * 4 + lg) ^ lr) << 4);
+
+  u32x4 wr[PF][NW][4];
+  u32x4 xr[PF][MT][4];
+  f32x4 acc[NW][MT];
+#pragma unroll
+  for (int s = 0; s < NW; ++s)
+#pragma unroll
+    for (int t = 0; t < MT; ++t) acc[s][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+#define LS_LOAD_BLOCK(slot, blk)                                                                 \
+  {                                                                                              \
+    const size_t kb_ = (size_t)(blk) << 7;                                                       \
+    _Pragma("unroll") for (int t_ = 0; t_ < MT; ++t_)                                            \
+      _Pragma("unroll") for (int k_ = 0; k_ < 4; ++k_)                                           \
+        xr[slot][t_][k_] = *reinterpret_cast<const u32x4*>(X + xoff[t_] + kb_ + k_ * 32);        \
+    _Pragma("unroll") for (int s_ = 0; s_ < NW; ++s_)                                            \
+      _Pragma("unroll") for (int i_ = 0; i_ < 4; ++i_)                                           \
+        wr[slot][s_][i_] = *reinterpret_cast<const u32x4*>(W + woff[s_][i_] + kb_);              \
+  }
+
+#pragma unroll
+  for (int p = 0; p < PF; ++p)
+    if (p < nb) LS_LOAD_BLOCK(p, b0 + p)
+
+  for (int b = 0; b < nb; b += PF) {
+#pragma unroll
+    for (int sl = 0; sl < PF; ++sl) {
+      if (b + sl < nb) {
+        // registers -> wave-private LDS scratch (lane-linear: conflict free)
+#pragma unroll
+        for (int s = 0; s < NW; ++s)
+#pragma unroll
+          for (int i = 0; i < 4; ++i)
+            *reinterpret_cast<u32x4*>(scratch + s * 4096 + i * 1024 + lane * 16) = wr[sl][s][i];
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+#pragma unroll
+          for (int s = 0; s < NW; ++s) {
+            const bf16x8 af = *reinterpret_cast<const bf16x8*>(scratch + s * 4096 + a_off[kk]);
+#pragma unroll
+            for (int t = 0; t < MT; ++t)
+              acc[s][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                  af, __builtin_bit_cast(bf16x8, xr[sl][t][kk]), acc[s][t], 0, 0, 0);
+          }
+        }
+        // refill this ring slot with the block PF ahead
+        if (b + sl + PF < nb) LS_LOAD_BLOCK(sl, b0 + b + sl + PF)
+      }
+    }
+  }
+#undef LS_LOAD_BLOCK
+
+  // ---- sum the KS partial tiles in wave order, then the epilogue
+  __syncthreads();  // every wave is done with its scratch; reuse LDS for the partials
+  float* red = reinterpret_cast<float*>(smem);  // [KS][NW][MT][16 m][16 n]
+#pragma unroll
+  for (int s = 0; s < NW; ++s)
+#pragma unroll
+    for (int t = 0; t < MT; ++t)
+      *reinterpret_cast<f32x4*>(red + ((((wave * NW + s) * MT + t) * 16 + lr) * 16 + lg * 4)) = acc[s][t];
+  __syncthreads();
+  for (int e = threadIdx.x; e < MT * 256; e += KS * 64) {
+    const int t = e >> 8, ml = (e >> 4) & 15, n = e & 15;
+    const int m = t * 16 + ml;
+    if (m >= M) continue;
+    float v[NW];
+#pragma unroll
+    for (int s = 0; s < NW; ++s) {
+      float sum = 0.f;
+#pragma unroll
+      for (int w = 0; w < KS; ++w) sum += red[(((w * NW + s) * MT + t) * 16 + ml) * 16 + n];
+      v[s] = sum;
+    }
+    const size_t o = (size_t)m * N + n0 + n;
+    if constexpr (EPI == EPI_STORE) ((bf16*)outv)[o] = (bf16)v[0];
+    else if constexpr (EPI == EPI_RESID) resid[o] += v[0];
+    else if constexpr (EPI == EPI_SWIGLU) ((bf16*)outv)[o] = (bf16)(silu_f(v[0]) * v[NW - 1]);
+    else ((float*)outv)[o] = v[0];
+  }
+}
+
+#ifndef LS_SKINNY_PF
+#define LS_SKINNY_PF 0
+#endif
+template <int MT, int EPI, int KS>
+void launch_k(const void* X, const void* W, int M, int N, int K, void* out, float* resid, hipStream_t st) {
+  constexpr int NW = (EPI == EPI_SWIGLU) ? 2 : 1;
+  constexpr int scratch = KS * NW * 4096, red = KS * NW * MT * 1024;
+  constexpr int smem = scratch > red ? scratch : red;
+  // register ring depth in 128-wide K blocks
+  constexpr int PF = LS_SKINNY_PF ? LS_SKINNY_PF : ((NW * 4 + MT * 4 <= 8 && KS < 16) ? 4 : 2);
+  static bool attr_set = false;
+  if (!attr_set) {
+    (void)hipFuncSetAttribute((const void*)k_gemm_skinny<MT, EPI, KS, PF>, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    attr_set = true;
+  }
+  k_gemm_skinny<MT, EPI, KS, PF><<<N / 16, KS * 64, smem, st>>>((const bf16*)X, (const bf16*)W, M, N, K, out, resid);
+}
+
+template <int MT, int EPI>
+void launch_ks(const void* X, const void* W, int M, int N, int K, void* out, float* resid, int ks, hipStream_t st) {
+  if (ks == 0) {
+    // enough wavefronts to fill 256 CUs with several each, but at least two K blocks per wave
+    const int tiles = N / 16, nblk = K / 128;
+    ks = 4;
+    while (ks < 16 && tiles * ks < 4096 && nblk / (ks * 2) >= 2) ks *= 2;
+  }
+  // 1024-thread workgroups leave too few registers for wide M or for two weight streams
+  if (ks == 16 && (MT > 1 || EPI == EPI_SWIGLU)) ks = 8;
+  if (ks == 8 && MT == 4 && EPI == EPI_SWIGLU) ks = 4;
+  if (ks == 4) launch_k<MT, EPI, 4>(X, W, M, N, K, out, resid, st);
+  else if (ks == 8) launch_k<MT, EPI, 8>(X, W, M, N, K, out, resid, st);
+  else if constexpr (MT == 1) launch_k<MT, EPI, 16>(X, W, M, N, K, out, resid, st);
+}
+
+template <int EPI>
+void launch_mt(const void* X, const void* W, int M, int N, int K, void* out, float* resid, int ks, hipStream_t st) {
+  if (M <= 16) launch_ks<1, EPI>(X, W, M, N, K, out, resid, ks, st);
+  else if (M <= 32) launch_ks<2, EPI>(X, W, M, N, K, out, resid, ks, st);
+  else launch_ks<4, EPI>(X, W, M, N, K, out, resid, ks, st);
+}
+
+}  // namespace
+
+bool gemm_skinny_supported(int M, int N, int K) {
+  return M >= 1 && M <= 64 && N >= 16 && N % 16 == 0 && K >= 512 && K % 128 == 0;
+}
+
+void launch_gemm_skinny(Epilogue epi, const void* X, const void* W, int M, int N, int K, void* out, float* resid,
+                        int ks, hipStream_t st) {
+  switch (epi) {
+    case EPI_STORE: launch_mt<EPI_STORE>(X, W, M, N, K, out, resid, ks, st); break;
+    case EPI_RESID: launch_mt<EPI_RESID>(X, W, M, N, K, out, resid, ks, st); break;
+    case EPI_SWIGLU: launch_mt<EPI_SWIGLU>(X, W, M, N, K, out, resid, ks, st); break;
+    case EPI_F32: launch_mt<EPI_F32>(X, W, M, N, K, out, resid, ks, st); break;
+  }
+}
+
+}  // namespace ls

@@ -47,6 +47,12 @@ bool gemm_mfma_supported(int M, int N, int K);
 void launch_gemm_mfma(Epilogue epi, const void* A, const void* W, int M, int N, int K, void* out, float* resid,
                       hipStream_t st);
 
+// bf16 weight-streaming kernel for decode steps (M <= 64); needs N % 16 == 0, K % 128 == 0.
+// ks = wavefronts that split K inside a workgroup (4, 8, 16), 0 = chosen from the shape.
+bool gemm_skinny_supported(int M, int N, int K);
+void launch_gemm_skinny(Epilogue epi, const void* X, const void* W, int M, int N, int K, void* out, float* resid,
+                        int ks, hipStream_t st);
+
 // Rotate q (in place inside qkv) and k by the per-position cos/sin table, write k and v
 // into the cache at [seq][kv head][pos].  qkv is [rows, (Hq+2Hkv)*hd].
 void launch_rope_append(uint32_t dt, void* qkv, const float* cs_table, const int32_t* row_seq,
