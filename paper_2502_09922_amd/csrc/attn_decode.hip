@@ -1,0 +1,176 @@
+// bf16 decode attention: one query row per sequence against its KV cache (GQA aware).
+//
+// Bound by streaming the cache out of HBM once per step, so: one workgroup per (sequence,
+// kv head) reads that head's keys and values exactly once for all G = Hq/Hkv query heads
+// that share it.  Its NW wavefronts split the context into contiguous ranges (split-KV
+// inside the workgroup).  A 16-byte-per-lane load instruction fetches 64/LPK consecutive
+// cache rows (LPK = head_dim/8 lanes per key, whole rows, 1 KB contiguous).  Each lane
+// keeps the partial dot product of its 8 dimensions, a butterfly over the LPK lanes of a key
+// completes the score, and every key slot runs its own online softmax (running max and sum)
+// so that no cross-slot traffic is needed inside the loop.  Slots are merged by shuffles,
+// wavefronts through LDS in wave order: the result does not depend on timing.
+#include "kernels.hpp"
+#include "device_util.hpp"
+
+namespace ls {
+
+namespace {
+
+constexpr int NW = 8;  // wavefronts per workgroup = context splits
+
+template <int HD, int G>
+__global__ void __launch_bounds__(NW * 64)
+k_attn_decode(const bf16* __restrict__ qkv, int qkv_stride, const bf16* __restrict__ kc,
+              const bf16* __restrict__ vc, const int32_t* __restrict__ row_seq,
+              const int32_t* __restrict__ row_pos, int hkv, int max_seq, bf16* __restrict__ out) {
+  constexpr int LPK = HD / 8;     // lanes per key
+  constexpr int KPI = 64 / LPK;   // keys per load instruction
+  constexpr int U = 4;            // load instructions in flight per operand
+  __shared__ float sm_m[NW][G], sm_l[NW][G];
+  __shared__ float sm_acc[NW][G][HD];
+  const int r = blockIdx.x, kh = blockIdx.y;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int pos = row_pos[r];
+  if (pos < 0) return;  // a sequence with no room left: whole workgroup leaves together
+  const int seq = row_seq[r];
+  const int ctx = pos + 1;
+  const int slot = lane / LPK, dl = lane % LPK;
+  const bf16* kb = kc + ((size_t)seq * hkv + kh) * max_seq * HD;
+  const bf16* vb = vc + ((size_t)seq * hkv + kh) * max_seq * HD;
+
+  // this lane's 8 dimensions of every query head of the group, pre-scaled
+  const float scale = 1.0f / sqrtf((float)HD);
+  float q[G][8];
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+    const bf16x8 qv = *reinterpret_cast<const bf16x8*>(qkv + (size_t)r * qkv_stride + (size_t)(kh * G + g) * HD + dl * 8);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) q[g][e] = (float)qv[e] * scale;
+  }
+
+  // contiguous key range of this wave, a multiple of KPI keys
+  const int chunk = ((ctx + NW * KPI - 1) / (NW * KPI)) * KPI;
+  const int k_begin = wave * chunk, k_end = min(k_begin + chunk, ctx);
+
+  float m[G], l[G], acc[G][8];
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+    m[g] = -INFINITY;
+    l[g] = 0.f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[g][e] = 0.f;
+  }
+
+  for (int j0 = k_begin; j0 < k_end; j0 += KPI * U) {
+    bf16x8 kf[U], vf[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int key = min(j0 + u * KPI + slot, ctx - 1);  // clamped: always a valid cache row
+      kf[u] = *reinterpret_cast<const bf16x8*>(kb + (size_t)key * HD + dl * 8);
+      vf[u] = *reinterpret_cast<const bf16x8*>(vb + (size_t)key * HD + dl * 8);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const bool valid = (j0 + u * KPI + slot) < k_end;
+      float kx[8], vx[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) { kx[e] = (float)kf[u][e]; vx[e] = (float)vf[u][e]; }
+#pragma unroll
+      for (int g = 0; g < G; ++g) {
+        float s = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) s = fmaf(q[g][e], kx[e], s);
+#pragma unroll
+        for (int off = LPK / 2; off; off >>= 1) s += __shfl_xor(s, off);
+        s = valid ? s : -INFINITY;
+        const float mn = fmaxf(m[g], s);
+        // mn == -inf only while this slot has seen no valid key: keep everything at zero
+        const float corr = (mn == -INFINITY) ? 1.f : __expf(m[g] - mn);
+        const float p = (mn == -INFINITY) ? 0.f : __expf(s - mn);
+        l[g] = l[g] * corr + p;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[g][e] = acc[g][e] * corr + p * vx[e];
+        m[g] = mn;
+      }
+    }
+  }
+
+  // merge the key slots of the wave (lanes that hold the same dimensions)
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+    float mw = m[g];
+#pragma unroll
+    for (int off = LPK; off < 64; off <<= 1) mw = fmaxf(mw, __shfl_xor(mw, off));
+    const float w = (m[g] == -INFINITY) ? 0.f : __expf(m[g] - mw);
+    float lw = l[g] * w;
+#pragma unroll
+    for (int off = LPK; off < 64; off <<= 1) lw += __shfl_xor(lw, off);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      float a = acc[g][e] * w;
+#pragma unroll
+      for (int off = LPK; off < 64; off <<= 1) a += __shfl_xor(a, off);
+      acc[g][e] = a;
+    }
+    if (lane < LPK) {
+      if (dl == 0) { sm_m[wave][g] = mw; sm_l[wave][g] = lw; }
+#pragma unroll
+      for (int e = 0; e < 8; ++e) sm_acc[wave][g][dl * 8 + e] = acc[g][e];
+    }
+  }
+  __syncthreads();
+
+  // merge the waves in wave order and write the output row
+  for (int i = threadIdx.x; i < G * HD; i += NW * 64) {
+    const int g = i / HD, d = i % HD;
+    float mm = -INFINITY;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) mm = fmaxf(mm, sm_m[w][g]);
+    float num = 0.f, den = 0.f;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) {
+      const float wt = (sm_m[w][g] == -INFINITY) ? 0.f : __expf(sm_m[w][g] - mm);
+      num += sm_acc[w][g][d] * wt;
+      den += sm_l[w][g] * wt;
+    }
+    out[(size_t)r * (hkv * G * HD) + (size_t)(kh * G + g) * HD + d] = (bf16)(num / den);
+  }
+}
+
+template <int HD, int G>
+void launch_g(const void* qkv, int qkv_stride, const void* kc, const void* vc, const int32_t* row_seq,
+              const int32_t* row_pos, int rows, int hkv, int max_seq, void* out, hipStream_t st) {
+  dim3 grid(rows, hkv);
+  k_attn_decode<HD, G><<<grid, NW * 64, 0, st>>>((const bf16*)qkv, qkv_stride, (const bf16*)kc, (const bf16*)vc,
+                                                  row_seq, row_pos, hkv, max_seq, (bf16*)out);
+}
+
+template <int HD>
+bool launch_hd(int g, const void* qkv, int qkv_stride, const void* kc, const void* vc, const int32_t* row_seq,
+               const int32_t* row_pos, int rows, int hkv, int max_seq, void* out, hipStream_t st) {
+  switch (g) {
+    case 1: launch_g<HD, 1>(qkv, qkv_stride, kc, vc, row_seq, row_pos, rows, hkv, max_seq, out, st); return true;
+    case 2: launch_g<HD, 2>(qkv, qkv_stride, kc, vc, row_seq, row_pos, rows, hkv, max_seq, out, st); return true;
+    case 4: launch_g<HD, 4>(qkv, qkv_stride, kc, vc, row_seq, row_pos, rows, hkv, max_seq, out, st); return true;
+    case 8: launch_g<HD, 8>(qkv, qkv_stride, kc, vc, row_seq, row_pos, rows, hkv, max_seq, out, st); return true;
+  }
+  return false;
+}
+
+}  // namespace
+
+bool attn_decode_supported(int hq, int hkv, int hd) {
+  const int g = hq / hkv;
+  return (hd == 128 || hd == 64) && (g == 1 || g == 2 || g == 4 || g == 8);
+}
+
+void launch_attn_decode(const void* qkv, int qkv_stride, const void* kc, const void* vc, const int32_t* row_seq,
+                        const int32_t* row_pos, int rows, int hq, int hkv, int hd, int max_seq, void* out,
+                        hipStream_t st) {
+  if (rows <= 0) return;
+  const int g = hq / hkv;
+  if (hd == 128) launch_hd<128>(g, qkv, qkv_stride, kc, vc, row_seq, row_pos, rows, hkv, max_seq, out, st);
+  else launch_hd<64>(g, qkv, qkv_stride, kc, vc, row_seq, row_pos, rows, hkv, max_seq, out, st);
+}
+
+}  // namespace ls

@@ -17,9 +17,13 @@ void launch_gemm(uint32_t dt, Epilogue epi, const void* A, const void* W, int M,
   launch_gemm_generic(dt, epi, A, W, M, N, K, out, resid, st);
 }
 
-void launch_attention(uint32_t dt, const void* qkv, int qkv_stride, const void* kcache, const void* vcache,
+void launch_attention(uint32_t dt, bool decode, const void* qkv, int qkv_stride, const void* kcache, const void* vcache,
                       const int32_t* row_seq, const int32_t* row_pos, int rows, int hq, int hkv, int hd,
                       int max_seq, void* out, hipStream_t st) {
+  if (dt == BF16 && decode && attn_decode_supported(hq, hkv, hd)) {
+    launch_attn_decode(qkv, qkv_stride, kcache, vcache, row_seq, row_pos, rows, hq, hkv, hd, max_seq, out, st);
+    return;
+  }
   launch_attention_generic(dt, qkv, qkv_stride, kcache, vcache, row_seq, row_pos, rows, hq, hkv, hd, max_seq, out, st);
 }
 
