@@ -355,7 +355,7 @@ ls_status ls_stage_set_profiling(ls_stage* s, int on) {
 // ---- the forward pass -------------------------------------------------------------------
 namespace {
 
-ls_status forward(ls_stage* s, bool prefill, const void* in, const int32_t* cu_dev, int batch, int rows,
+ls_status forward(ls_stage* s, bool prefill, const void* in, const int32_t* cu_dev, int batch, int rows, int max_len,
                   const ls_kv* kv, void* out, float* logits_out, hipStream_t st) {
   using namespace ls;
   const ls_cfg& c = s->cfg;
@@ -415,7 +415,7 @@ ls_status forward(ls_stage* s, bool prefill, const void* in, const int32_t* cu_d
     PROBE(LS_OP_GEMM_QKV, launch_gemm(dt, EPI_STORE, y, base + sp[1].off, rows, qkv_cols, d, qkv, nullptr, st));
     PROBE(LS_OP_ROPE, launch_rope_append(dt, qkv, cs, row_seq, row_pos, rows, hq, hkv, hd, c.max_seq, kc, vc, st));
     PROBE(LS_OP_ATTENTION,
-          launch_attention(dt, !prefill, qkv, qkv_cols, kc, vc, row_seq, row_pos, rows, hq, hkv, hd, c.max_seq, attn, st));
+          launch_attention(dt, cu_dev, batch, max_len, qkv, qkv_cols, kc, vc, row_seq, row_pos, rows, hq, hkv, hd, c.max_seq, attn, st));
     PROBE(LS_OP_GEMM_O, launch_gemm(dt, EPI_RESID, attn, base + sp[2].off, rows, d, hq * hd, nullptr, x, st));
     launch_rmsnorm(dt, x, base + sp[3].off, y, rows, d, c.rms_eps, nullptr, st);
     PROBE(LS_OP_GEMM_GATEUP, launch_gemm(dt, EPI_SWIGLU, y, base + sp[4].off, rows, F, d, hbuf, nullptr, st));
@@ -470,13 +470,15 @@ ls_status ls_stage_prefill(ls_stage* s, const void* in, const int32_t* cu_dev, c
     return fail(LS_ERR_INVALID_ARG, "ls_stage_prefill: total_tokens %d outside [%d,%u]", total_tokens, batch, s->cfg.max_tokens);
   if (cu_host[0] != 0 || cu_host[batch] != total_tokens)
     return fail(LS_ERR_INVALID_ARG, "ls_stage_prefill: cu_seqlens must start at 0 and end at total_tokens");
+  int max_len = 0;
   for (int b = 0; b < batch; ++b) {
     int len = cu_host[b + 1] - cu_host[b];
+    if (len > max_len) max_len = len;
     if (len < 1) return fail(LS_ERR_INVALID_ARG, "ls_stage_prefill: sequence %d has length %d", b, len);
     if (len > (int)s->cfg.max_seq)
       return fail(LS_ERR_KV_OVERFLOW, "ls_stage_prefill: sequence %d has %d tokens, max_seq is %u", b, len, s->cfg.max_seq);
   }
-  return forward(s, true, in, cu_dev, batch, total_tokens, kv, out, logits_out, (hipStream_t)hip_stream);
+  return forward(s, true, in, cu_dev, batch, total_tokens, max_len, kv, out, logits_out, (hipStream_t)hip_stream);
 }
 
 ls_status ls_stage_decode(ls_stage* s, const void* in, int batch, int max_ctx, const ls_kv* kv, void* out,
@@ -486,7 +488,7 @@ ls_status ls_stage_decode(ls_stage* s, const void* in, int batch, int max_ctx, c
   if (max_ctx < 0) return fail(LS_ERR_INVALID_ARG, "ls_stage_decode: max_ctx %d is negative", max_ctx);
   if (max_ctx + 1 > (int)s->cfg.max_seq)
     return fail(LS_ERR_KV_OVERFLOW, "ls_stage_decode: context %d + 1 exceeds max_seq %u", max_ctx, s->cfg.max_seq);
-  return forward(s, false, in, nullptr, batch, batch, kv, out, logits_out, (hipStream_t)hip_stream);
+  return forward(s, false, in, nullptr, batch, batch, 1, kv, out, logits_out, (hipStream_t)hip_stream);
 }
 
 ls_status ls_stage_layer_times(ls_stage* s, float* copy_ms, float* compute_ms, float* copy_end_ms,
