@@ -224,8 +224,7 @@ ls_status ls_stage_layer_times(ls_stage* stage, float* copy_ms, float* compute_m
 #define LS_OP_NONE 0
 #define LS_OP_NORM 1        /* attention RMSNorm                    */
 #define LS_OP_GEMM_QKV 2    /* y Wqkv^T                             */
-#define LS_OP_ROPE 3        /* RoPE + KV append                     */
-#define LS_OP_ATTENTION 4   /* causal attention                     */
+#define LS_OP_ATTENTION 4   /* RoPE + KV append + causal attention  */
 #define LS_OP_GEMM_O 5      /* x += o Wo^T                          */
 #define LS_OP_GEMM_GATEUP 6 /* silu(y Wg^T) * (y Wu^T)              */
 #define LS_OP_GEMM_DOWN 7   /* x += h Wd^T                          */

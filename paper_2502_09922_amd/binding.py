@@ -30,8 +30,8 @@ lib = C.CDLL(LIB_PATH)
 LS_ABI_VERSION = 1
 LS_DTYPE_F32, LS_DTYPE_BF16 = 0, 1
 LS_BLOCK_EMBED = -1
-(LS_OP_NONE, LS_OP_NORM, LS_OP_GEMM_QKV, LS_OP_ROPE, LS_OP_ATTENTION, LS_OP_GEMM_O,
- LS_OP_GEMM_GATEUP, LS_OP_GEMM_DOWN) = range(8)
+LS_OP_NONE, LS_OP_NORM, LS_OP_GEMM_QKV = 0, 1, 2
+LS_OP_ATTENTION, LS_OP_GEMM_O, LS_OP_GEMM_GATEUP, LS_OP_GEMM_DOWN = 4, 5, 6, 7
 (LS_OK, LS_ERR_INVALID_ARG, LS_ERR_BLOCK_RANGE, LS_ERR_NOT_LOADED, LS_ERR_ALREADY_LOADED,
  LS_ERR_KV_OVERFLOW, LS_ERR_OOM, LS_ERR_HIP) = (0, -1, -2, -3, -4, -5, -6, -7)
 

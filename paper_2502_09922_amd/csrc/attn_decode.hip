@@ -1,4 +1,11 @@
-// bf16 decode attention: one query row per sequence against its KV cache (GQA aware).
+// bf16 decode attention, fused with RoPE and the KV-cache append of the new row: one query
+// row per sequence against its KV cache (GQA aware).
+//
+// The step's q, k, v are read un-rotated from the projection output.  q is rotated in
+// registers; the new key is rotated, rounded to bf16 and written to the cache row `pos`
+// together with the new value by wave 0, which also feeds them to its own softmax state
+// straight from registers -- no wavefront of this kernel reads cache row `pos`, so there is
+// no ordering problem between that store and the streaming loads.
 //
 // Bound by streaming the cache out of HBM once per step, so: one workgroup per (sequence,
 // kv head) reads that head's keys and values exactly once for all G = Hq/Hkv query heads
@@ -20,9 +27,9 @@ constexpr int NW = 8;  // wavefronts per workgroup = context splits
 
 template <int HD, int G>
 __global__ void __launch_bounds__(NW * 64)
-k_attn_decode(const bf16* __restrict__ qkv, int qkv_stride, const bf16* __restrict__ kc,
-              const bf16* __restrict__ vc, const int32_t* __restrict__ row_seq,
-              const int32_t* __restrict__ row_pos, int hkv, int max_seq, bf16* __restrict__ out) {
+k_attn_decode(const bf16* __restrict__ qkv, int qkv_stride, const float2* __restrict__ cs,
+              bf16* __restrict__ kc, bf16* __restrict__ vc, const int32_t* __restrict__ row_seq,
+              const int32_t* __restrict__ row_pos, int hq, int hkv, int max_seq, bf16* __restrict__ out) {
   constexpr int LPK = HD / 8;     // lanes per key
   constexpr int KPI = 64 / LPK;   // keys per load instruction
   constexpr int U = 4;            // load instructions in flight per operand
@@ -33,19 +40,29 @@ k_attn_decode(const bf16* __restrict__ qkv, int qkv_stride, const bf16* __restri
   const int pos = row_pos[r];
   if (pos < 0) return;  // a sequence with no room left: whole workgroup leaves together
   const int seq = row_seq[r];
-  const int ctx = pos + 1;
+  const int ctx = pos;  // keys 0..pos-1 come from the cache, key `pos` from this step's row
   const int slot = lane / LPK, dl = lane % LPK;
-  const bf16* kb = kc + ((size_t)seq * hkv + kh) * max_seq * HD;
-  const bf16* vb = vc + ((size_t)seq * hkv + kh) * max_seq * HD;
+  bf16* kb = kc + ((size_t)seq * hkv + kh) * max_seq * HD;
+  bf16* vb = vc + ((size_t)seq * hkv + kh) * max_seq * HD;
+  const bf16* row = qkv + (size_t)r * qkv_stride;
 
-  // this lane's 8 dimensions of every query head of the group, pre-scaled
+  // cos/sin of this lane's four pairs (dims 8 dl + 2i, 8 dl + 2i + 1) at position pos
+  float2 rot[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) rot[i] = cs[(size_t)pos * (HD / 2) + dl * 4 + i];
+
+  // this lane's 8 dimensions of every query head of the group: rotated, pre-scaled
   const float scale = 1.0f / sqrtf((float)HD);
   float q[G][8];
 #pragma unroll
   for (int g = 0; g < G; ++g) {
-    const bf16x8 qv = *reinterpret_cast<const bf16x8*>(qkv + (size_t)r * qkv_stride + (size_t)(kh * G + g) * HD + dl * 8);
+    const bf16x8 qv = *reinterpret_cast<const bf16x8*>(row + (size_t)(kh * G + g) * HD + dl * 8);
 #pragma unroll
-    for (int e = 0; e < 8; ++e) q[g][e] = (float)qv[e] * scale;
+    for (int i = 0; i < 4; ++i) {
+      const float u0 = (float)qv[2 * i], u1 = (float)qv[2 * i + 1];
+      q[g][2 * i] = (u0 * rot[i].x - u1 * rot[i].y) * scale;
+      q[g][2 * i + 1] = (u0 * rot[i].y + u1 * rot[i].x) * scale;
+    }
   }
 
   // contiguous key range of this wave, a multiple of KPI keys
@@ -59,6 +76,22 @@ k_attn_decode(const bf16* __restrict__ qkv, int qkv_stride, const bf16* __restri
     l[g] = 0.f;
 #pragma unroll
     for (int e = 0; e < 8; ++e) acc[g][e] = 0.f;
+  }
+
+  // one key per slot: scores of the G heads, then the slot's online-softmax update
+#define LS_KEY_UPDATE(kx, vx, valid)                                                         \
+  _Pragma("unroll") for (int g = 0; g < G; ++g) {                                            \
+    float s_ = 0.f;                                                                          \
+    _Pragma("unroll") for (int e = 0; e < 8; ++e) s_ = fmaf(q[g][e], kx[e], s_);             \
+    _Pragma("unroll") for (int off = LPK / 2; off; off >>= 1) s_ += __shfl_xor(s_, off);     \
+    s_ = (valid) ? s_ : -INFINITY;                                                           \
+    const float mn_ = fmaxf(m[g], s_);                                                       \
+    /* mn_ == -inf only while this slot has seen no valid key: keep everything at zero */    \
+    const float corr_ = (mn_ == -INFINITY) ? 1.f : __expf(m[g] - mn_);                       \
+    const float p_ = (mn_ == -INFINITY) ? 0.f : __expf(s_ - mn_);                            \
+    l[g] = l[g] * corr_ + p_;                                                                \
+    _Pragma("unroll") for (int e = 0; e < 8; ++e) acc[g][e] = acc[g][e] * corr_ + p_ * vx[e]; \
+    m[g] = mn_;                                                                              \
   }
 
   for (int j0 = k_begin; j0 < k_end; j0 += KPI * U) {
@@ -75,25 +108,32 @@ k_attn_decode(const bf16* __restrict__ qkv, int qkv_stride, const bf16* __restri
       float kx[8], vx[8];
 #pragma unroll
       for (int e = 0; e < 8; ++e) { kx[e] = (float)kf[u][e]; vx[e] = (float)vf[u][e]; }
-#pragma unroll
-      for (int g = 0; g < G; ++g) {
-        float s = 0.f;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) s = fmaf(q[g][e], kx[e], s);
-#pragma unroll
-        for (int off = LPK / 2; off; off >>= 1) s += __shfl_xor(s, off);
-        s = valid ? s : -INFINITY;
-        const float mn = fmaxf(m[g], s);
-        // mn == -inf only while this slot has seen no valid key: keep everything at zero
-        const float corr = (mn == -INFINITY) ? 1.f : __expf(m[g] - mn);
-        const float p = (mn == -INFINITY) ? 0.f : __expf(s - mn);
-        l[g] = l[g] * corr + p;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) acc[g][e] = acc[g][e] * corr + p * vx[e];
-        m[g] = mn;
-      }
+      LS_KEY_UPDATE(kx, vx, valid)
     }
   }
+
+  // the new row: rotate k, round both to bf16, append to the cache, attend to it
+  if (wave == 0) {
+    const bf16x8 kn = *reinterpret_cast<const bf16x8*>(row + (size_t)(hq + kh) * HD + dl * 8);
+    const bf16x8 vn = *reinterpret_cast<const bf16x8*>(row + (size_t)(hq + hkv + kh) * HD + dl * 8);
+    bf16x8 kr;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const float u0 = (float)kn[2 * i], u1 = (float)kn[2 * i + 1];
+      kr[2 * i] = (bf16)(u0 * rot[i].x - u1 * rot[i].y);
+      kr[2 * i + 1] = (bf16)(u0 * rot[i].y + u1 * rot[i].x);
+    }
+    if (slot == 0) {
+      *reinterpret_cast<bf16x8*>(kb + (size_t)pos * HD + dl * 8) = kr;
+      *reinterpret_cast<bf16x8*>(vb + (size_t)pos * HD + dl * 8) = vn;
+    }
+    float kx[8], vx[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { kx[e] = (float)kr[e]; vx[e] = (float)vn[e]; }
+    const bool valid = slot == 0;
+    LS_KEY_UPDATE(kx, vx, valid)
+  }
+#undef LS_KEY_UPDATE
 
   // merge the key slots of the wave (lanes that hold the same dimensions)
 #pragma unroll
@@ -138,21 +178,21 @@ k_attn_decode(const bf16* __restrict__ qkv, int qkv_stride, const bf16* __restri
 }
 
 template <int HD, int G>
-void launch_g(const void* qkv, int qkv_stride, const void* kc, const void* vc, const int32_t* row_seq,
+void launch_g(const void* qkv, int qkv_stride, const float* cs, void* kc, void* vc, const int32_t* row_seq,
               const int32_t* row_pos, int rows, int hkv, int max_seq, void* out, hipStream_t st) {
   dim3 grid(rows, hkv);
-  k_attn_decode<HD, G><<<grid, NW * 64, 0, st>>>((const bf16*)qkv, qkv_stride, (const bf16*)kc, (const bf16*)vc,
-                                                  row_seq, row_pos, hkv, max_seq, (bf16*)out);
+  k_attn_decode<HD, G><<<grid, NW * 64, 0, st>>>((const bf16*)qkv, qkv_stride, (const float2*)cs, (bf16*)kc, (bf16*)vc,
+                                                  row_seq, row_pos, hkv * G, hkv, max_seq, (bf16*)out);
 }
 
 template <int HD>
-bool launch_hd(int g, const void* qkv, int qkv_stride, const void* kc, const void* vc, const int32_t* row_seq,
+bool launch_hd(int g, const void* qkv, int qkv_stride, const float* cs, void* kc, void* vc, const int32_t* row_seq,
                const int32_t* row_pos, int rows, int hkv, int max_seq, void* out, hipStream_t st) {
   switch (g) {
-    case 1: launch_g<HD, 1>(qkv, qkv_stride, kc, vc, row_seq, row_pos, rows, hkv, max_seq, out, st); return true;
-    case 2: launch_g<HD, 2>(qkv, qkv_stride, kc, vc, row_seq, row_pos, rows, hkv, max_seq, out, st); return true;
-    case 4: launch_g<HD, 4>(qkv, qkv_stride, kc, vc, row_seq, row_pos, rows, hkv, max_seq, out, st); return true;
-    case 8: launch_g<HD, 8>(qkv, qkv_stride, kc, vc, row_seq, row_pos, rows, hkv, max_seq, out, st); return true;
+    case 1: launch_g<HD, 1>(qkv, qkv_stride, cs, kc, vc, row_seq, row_pos, rows, hkv, max_seq, out, st); return true;
+    case 2: launch_g<HD, 2>(qkv, qkv_stride, cs, kc, vc, row_seq, row_pos, rows, hkv, max_seq, out, st); return true;
+    case 4: launch_g<HD, 4>(qkv, qkv_stride, cs, kc, vc, row_seq, row_pos, rows, hkv, max_seq, out, st); return true;
+    case 8: launch_g<HD, 8>(qkv, qkv_stride, cs, kc, vc, row_seq, row_pos, rows, hkv, max_seq, out, st); return true;
   }
   return false;
 }
@@ -164,13 +204,13 @@ bool attn_decode_supported(int hq, int hkv, int hd) {
   return (hd == 128 || hd == 64) && (g == 1 || g == 2 || g == 4 || g == 8);
 }
 
-void launch_attn_decode(const void* qkv, int qkv_stride, const void* kc, const void* vc, const int32_t* row_seq,
-                        const int32_t* row_pos, int rows, int hq, int hkv, int hd, int max_seq, void* out,
-                        hipStream_t st) {
+void launch_attn_decode(const void* qkv, int qkv_stride, const float* cs_table, void* kc, void* vc,
+                        const int32_t* row_seq, const int32_t* row_pos, int rows, int hq, int hkv, int hd,
+                        int max_seq, void* out, hipStream_t st) {
   if (rows <= 0) return;
   const int g = hq / hkv;
-  if (hd == 128) launch_hd<128>(g, qkv, qkv_stride, kc, vc, row_seq, row_pos, rows, hkv, max_seq, out, st);
-  else launch_hd<64>(g, qkv, qkv_stride, kc, vc, row_seq, row_pos, rows, hkv, max_seq, out, st);
+  if (hd == 128) launch_hd<128>(g, qkv, qkv_stride, cs_table, kc, vc, row_seq, row_pos, rows, hkv, max_seq, out, st);
+  else launch_hd<64>(g, qkv, qkv_stride, cs_table, kc, vc, row_seq, row_pos, rows, hkv, max_seq, out, st);
 }
 
 }  // namespace ls

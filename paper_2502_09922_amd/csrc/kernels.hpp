@@ -61,13 +61,22 @@ void launch_rope_append(uint32_t dt, void* qkv, const float* cs_table, const int
 
 // Causal attention of every row against its sequence's cache positions 0..row_pos[r].
 // q is read from qkv ([rows, qkv_stride]); out is [rows, Hq*hd].
+// Attention of one layer, including RoPE and the KV-cache append of the call's rows.
+// qkv [rows, (Hq+2Hkv)*hd] holds the un-rotated projections and may be rotated in place.
 // Decode (cu_seqlens == nullptr): every row is the single new row of its sequence.
 // Prefill: sequence b owns rows [cu_seqlens[b], cu_seqlens[b+1]) at positions 0.., the
-// longest sequence has max_len rows.
-void launch_attention(uint32_t dt, const int32_t* cu_seqlens, int batch, int max_len, const void* qkv,
-                      int qkv_stride, const void* kcache, const void* vcache, const int32_t* row_seq,
-                      const int32_t* row_pos, int rows, int hq, int hkv, int hd, int max_seq, void* out,
-                      hipStream_t st);
+// longest sequence has max_len rows.  out is [rows, Hq*hd].
+void launch_attention_block(uint32_t dt, const int32_t* cu_seqlens, int batch, int max_len, void* qkv,
+                            const float* cs_table, void* kcache, void* vcache, const int32_t* row_seq,
+                            const int32_t* row_pos, int rows, int hq, int hkv, int hd, int max_seq, void* out,
+                            hipStream_t st);
+
+// bf16 split-KV decode attention fused with RoPE and the cache append; head_dim 64 or 128,
+// Hq/Hkv in {1,2,4,8}.
+bool attn_decode_supported(int hq, int hkv, int hd);
+void launch_attn_decode(const void* qkv, int qkv_stride, const float* cs_table, void* kc, void* vc,
+                        const int32_t* row_seq, const int32_t* row_pos, int rows, int hq, int hkv, int hd,
+                        int max_seq, void* out, hipStream_t st);
 
 // bf16 flash-style causal attention for the prompt pass; head_dim 64 or 128.
 bool attn_prefill_supported(int hq, int hkv, int hd);

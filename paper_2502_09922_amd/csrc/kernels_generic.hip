@@ -126,11 +126,51 @@ __global__ void __launch_bounds__(256) k_rmsnorm(const float* __restrict__ x, co
   for (int i = threadIdx.x; i < d; i += 256) yr[i] = from_f<T>(xr[i] * inv * to_f(gamma[i]));
 }
 
+// Fast path for d % 4 == 0 and d <= 8192: the row lives in registers (up to eight 16-byte
+// loads per thread, all issued before the first use), so x is read exactly once.
+template <class T>
+__global__ void __launch_bounds__(256) k_rmsnorm_vec(const float* __restrict__ x, const T* __restrict__ gamma,
+                                                     T* __restrict__ y, int d, float eps,
+                                                     const int32_t* __restrict__ row_map) {
+  __shared__ float part[4];
+  const int r = blockIdx.x, nv = d >> 2;
+  const f32x4* xr = reinterpret_cast<const f32x4*>(x + (size_t)(row_map ? row_map[r] : r) * d);
+  f32x4 v[8];
+  float ss = 0.f;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const int idx = threadIdx.x + 256 * i;
+    v[i] = idx < nv ? xr[idx] : f32x4{0.f, 0.f, 0.f, 0.f};
+  }
+#pragma unroll
+  for (int i = 0; i < 8; ++i) ss += v[i][0] * v[i][0] + v[i][1] * v[i][1] + v[i][2] * v[i][2] + v[i][3] * v[i][3];
+  ss = wave_sum(ss);
+  if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = ss;
+  __syncthreads();
+  const float tot = (part[0] + part[1]) + (part[2] + part[3]);
+  const float inv = 1.0f / sqrtf(tot / (float)d + eps);
+  T* yr = y + (size_t)r * d;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const int idx = threadIdx.x + 256 * i;
+    if (idx < nv) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) yr[idx * 4 + e] = from_f<T>(v[i][e] * inv * to_f(gamma[idx * 4 + e]));
+    }
+  }
+}
+
 void launch_rmsnorm(uint32_t dt, const float* x, const void* gamma, void* y, int rows, int d,
                     float eps, const int32_t* row_map, hipStream_t st) {
   if (rows <= 0) return;
-  if (dt == F32) k_rmsnorm<float><<<rows, 256, 0, st>>>(x, (const float*)gamma, (float*)y, d, eps, row_map);
-  else k_rmsnorm<bf16><<<rows, 256, 0, st>>>(x, (const bf16*)gamma, (bf16*)y, d, eps, row_map);
+  const bool vec = (d % 4 == 0) && d <= 8192;
+  if (dt == F32) {
+    if (vec) k_rmsnorm_vec<float><<<rows, 256, 0, st>>>(x, (const float*)gamma, (float*)y, d, eps, row_map);
+    else k_rmsnorm<float><<<rows, 256, 0, st>>>(x, (const float*)gamma, (float*)y, d, eps, row_map);
+  } else {
+    if (vec) k_rmsnorm_vec<bf16><<<rows, 256, 0, st>>>(x, (const bf16*)gamma, (bf16*)y, d, eps, row_map);
+    else k_rmsnorm<bf16><<<rows, 256, 0, st>>>(x, (const bf16*)gamma, (bf16*)y, d, eps, row_map);
+  }
 }
 
 // ------------------------------------------------------------------ generic GEMM

@@ -413,9 +413,8 @@ ls_status forward(ls_stage* s, bool prefill, const void* in, const int32_t* cu_d
 
     PROBE(LS_OP_NORM, launch_rmsnorm(dt, x, base + sp[0].off, y, rows, d, c.rms_eps, nullptr, st));
     PROBE(LS_OP_GEMM_QKV, launch_gemm(dt, EPI_STORE, y, base + sp[1].off, rows, qkv_cols, d, qkv, nullptr, st));
-    PROBE(LS_OP_ROPE, launch_rope_append(dt, qkv, cs, row_seq, row_pos, rows, hq, hkv, hd, c.max_seq, kc, vc, st));
-    PROBE(LS_OP_ATTENTION,
-          launch_attention(dt, cu_dev, batch, max_len, qkv, qkv_cols, kc, vc, row_seq, row_pos, rows, hq, hkv, hd, c.max_seq, attn, st));
+    PROBE(LS_OP_ATTENTION, launch_attention_block(dt, cu_dev, batch, max_len, qkv, cs, kc, vc, row_seq, row_pos, rows,
+                                                  hq, hkv, hd, c.max_seq, attn, st));
     PROBE(LS_OP_GEMM_O, launch_gemm(dt, EPI_RESID, attn, base + sp[2].off, rows, d, hq * hd, nullptr, x, st));
     launch_rmsnorm(dt, x, base + sp[3].off, y, rows, d, c.rms_eps, nullptr, st);
     PROBE(LS_OP_GEMM_GATEUP, launch_gemm(dt, EPI_SWIGLU, y, base + sp[4].off, rows, F, d, hbuf, nullptr, st));
