@@ -60,15 +60,15 @@ def st_block_bytes(st, layer):
     return b.ls_stage_block_bytes(st.handle, layer)
 
 
-def cpu_baseline(synth, shape, lo, batch):
+def cpu_baseline(synth, shape, lo, batch, prompt, dsteps):
     """The oracle as it stands, timed on this machine's host cores on a bounded sample of the
-    same workload: ONE layer at the real dimensions, `batch` sequences of 64 prompt tokens
-    and 2 decode steps; scaled linearly in layers to the stage (extrapolated)."""
+    same workload: ONE layer at the real dimensions, the full batch and prompt length and 8
+    decode steps; scaled linearly in layers to the stage (extrapolated)."""
     from oracle.stage_oracle import OracleStage
 
     import threadpoolctl
 
-    n_prompt, n_dec = 64, 2
+    n_prompt, n_dec = prompt, min(8, dsteps)
     one = shape.with_(vocab=0)
     ora = OracleStage(one, lo, lo + 1, batch, n_prompt + n_dec)
     ora.load_tensors(lo, synth.layer_tensors(one, SEED, lo))
@@ -216,7 +216,7 @@ def main():
                              "flops_per_launch": pg_flops, "avg_ms": pg_ms, "launches_timed": len(probe_pre)},
     }
     if not args.no_cpu_baseline:
-        dt, ntok, threads, n_prompt, n_dec = cpu_baseline(synth, shape, lo, batch)
+        dt, ntok, threads, n_prompt, n_dec = cpu_baseline(synth, shape, lo, batch, prompt, dsteps)
         res["cpu_baseline"] = {
             "value": ntok / (dt * L), "unit": "tokens/s", "cores": threads, "kind": "oracle",
             "sample": "1 of %d layers at real dims, %d seqs x (%d prompt + %d decode) tokens in %.1f s; "
