@@ -201,3 +201,42 @@ def test_runtime_errors_enqueue_nothing():
         st.prefill(tok, [8])
     assert e.value.status == b.LS_ERR_NOT_LOADED
     st.close()
+
+
+def test_layer_times_show_the_gate_and_the_overlap():
+    """With profiling on, every layer's kernels end after that layer's block copy ended
+    (the gate), copies and layers have positive durations, and completion times rise with
+    the layer index."""
+    import torch
+    from paper_2502_09922_amd import LsError, binding as b
+
+    shape, seed, lengths = MINI_BF16, 13, [100, 60]
+    B, S = len(lengths), max(lengths)
+    st = make_gpu(shape, seed, 0, 3, B, S + 1, sum(lengths), load=False)
+    with pytest.raises(LsError):  # nothing recorded yet
+        st.layer_times()
+    blocks = {l: st.stage_host_block(l, buf) for l, buf in packed_blocks(st, seed).items()}
+    tok = to_dev(shape, synth.token_ids(seed + 1, sum(lengths), shape.vocab))
+    st.set_profiling(True)
+    copy_stream = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    for l in st.block_ids():
+        st.load_block(l, blocks[l], stream=copy_stream)
+    st.prefill(tok, lengths)
+    torch.cuda.synchronize()
+    lt = st.layer_times()
+    assert all(c > 0 for c in lt["copy_ms"]) and all(p > 0 for p in lt["compute_ms"])
+    assert all(ce >= cp for ce, cp in zip(lt["compute_end_ms"], lt["copy_end_ms"]))
+    assert lt["compute_end_ms"] == sorted(lt["compute_end_ms"])
+    assert lt["copy_end_ms"] == sorted(lt["copy_end_ms"])
+    # the probe brackets one operator of one layer
+    st.probe(b.LS_OP_GEMM_QKV, 1, 0)
+    st.prefill(tok, lengths)
+    st.prefill(tok, lengths)
+    torch.cuda.synchronize()
+    times = st.probe_times()
+    assert len(times) == 2 and all(t > 0 for t in times)
+    st.probe(b.LS_OP_NONE)
+    with pytest.raises(LsError):
+        st.probe(b.LS_OP_GEMM_QKV, 7, 0)
+    st.close()
