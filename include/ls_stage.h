@@ -83,7 +83,7 @@ typedef struct {
  * (Section 5 leaves runtime state of dynamic size to the serving engine).
  *   k, v      [layer_hi-layer_lo][max_batch][n_kv_heads][max_seq][head_dim], dtype
  *   seq_lens  [max_batch] int32: positions already cached per sequence.  Prefill sets
- *             it, decode adds one, both on the device at the end of the call.
+ *             it, decode adds one, both on the device in the course of the call.
  */
 typedef struct {
   void* k;

@@ -15,6 +15,13 @@
 //     (column m = lane%16); a lane of the result holds m = lane%16, n = 4*(lane/16) + r.
 //   * The KS partial tiles are summed through LDS in wave order (fixed order: results are
 //     reproducible), then the epilogue stores, adds to the residual stream, or applies SwiGLU.
+//
+// Decode-step fusion of the RMSNorms (no separate norm launches):
+//   * a residual-add epilogue can also emit xb = bf16(x) and, per row and 16-column tile,
+//     the sum of squares of the new x (fp32, fixed-order reduction);
+//   * a NORM prologue takes that xb and those partial sums instead of a normalised input:
+//     the B operand is bf16(xb * gamma) (gamma staged per wave in LDS) and the accumulator
+//     is scaled by 1/sqrt(mean(x^2)+eps) of its row in the epilogue.
 #include "kernels.hpp"
 #include "device_util.hpp"
 
@@ -22,13 +29,14 @@ namespace ls {
 
 namespace {
 
-template <int MT, int EPI, int KS, int PF>
+template <int MT, int EPI, int KS, int PF, bool NORM>
 __global__ void __launch_bounds__(KS * 64)
 k_gemm_skinny(const bf16* __restrict__ X, const bf16* __restrict__ W, int M, int N, int K,
-              void* __restrict__ outv, float* __restrict__ resid) {
+              void* __restrict__ outv, float* __restrict__ resid, SkinnyFusion fu) {
   constexpr bool GLU = (EPI == EPI_SWIGLU);
   constexpr int NW = GLU ? 2 : 1;                      // weight streams per wave
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  __shared__ float sm_inv[MT * 16];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int lr = lane & 15, lg = lane >> 4;
   const int n0 = blockIdx.x * 16;
@@ -36,7 +44,9 @@ k_gemm_skinny(const bf16* __restrict__ X, const bf16* __restrict__ W, int M, int
   const int b0 = (int)((long)wave * nblk / KS), b1 = (int)((long)(wave + 1) * nblk / KS);
   const int nb = b1 - b0;
   unsigned char* scratch = smem + wave * (NW * 4096);
-
+  // NORM: this wave's slice of gamma lives behind the scratch areas of all waves
+  const int gam_stride = ((nblk + KS - 1) / KS + 1) * 256;
+  unsigned char* gam = smem + KS * (NW * 4096) + wave * gam_stride;
   // per-lane global offsets (elements) of the four load instructions of a block
   size_t woff[NW][4];
 #pragma unroll
@@ -76,6 +86,30 @@ k_gemm_skinny(const bf16* __restrict__ X, const bf16* __restrict__ W, int M, int
   for (int p = 0; p < PF; ++p)
     if (p < nb) LS_LOAD_BLOCK(p, b0 + p)
 
+  // (after the weight ring has been requested, so the stream starts first)
+  if constexpr (NORM) {
+    for (int i = lane; i < nb * 16; i += 64)
+      *reinterpret_cast<u32x4*>(gam + i * 16) = *reinterpret_cast<const u32x4*>(fu.gamma + (size_t)b0 * 128 + i * 8);
+    // 1/rms per row: the waves share the rows; a row's partial sums of squares are read with
+    // independent loads (lane i takes partials i, i+64, ...), added in that order, then
+    // combined by the fixed lane butterfly
+    for (int row = wave; row < M; row += KS) {
+      float pv[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int idx = lane + 64 * u;
+        pv[u] = idx < fu.n_part ? fu.ss_in[(size_t)row * fu.n_part + idx] : 0.f;
+      }
+      float ss = 0.f;
+#pragma unroll
+      for (int u = 0; u < 8; ++u) ss += pv[u];
+      for (int idx = lane + 512; idx < fu.n_part; idx += 64) ss += fu.ss_in[(size_t)row * fu.n_part + idx];
+      ss = wave_sum(ss);
+      if (lane == 0) sm_inv[row] = 1.0f / sqrtf(ss / (float)K + fu.eps);
+    }
+  }
+
+
   for (int b = 0; b < nb; b += PF) {
 #pragma unroll
     for (int sl = 0; sl < PF; ++sl) {
@@ -92,9 +126,15 @@ k_gemm_skinny(const bf16* __restrict__ X, const bf16* __restrict__ W, int M, int
           for (int s = 0; s < NW; ++s) {
             const bf16x8 af = *reinterpret_cast<const bf16x8*>(scratch + s * 4096 + a_off[kk]);
 #pragma unroll
-            for (int t = 0; t < MT; ++t)
-              acc[s][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                  af, __builtin_bit_cast(bf16x8, xr[sl][t][kk]), acc[s][t], 0, 0, 0);
+            for (int t = 0; t < MT; ++t) {
+              bf16x8 xf = __builtin_bit_cast(bf16x8, xr[sl][t][kk]);
+              if constexpr (NORM) {
+                const bf16x8 g8 = *reinterpret_cast<const bf16x8*>(gam + ((b + sl) * 128 + kk * 32 + lg * 8) * 2);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) xf[e] = (bf16)((float)xf[e] * (float)g8[e]);
+              }
+              acc[s][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af, xf, acc[s][t], 0, 0, 0);
+            }
           }
         }
         // refill this ring slot with the block PF ahead
@@ -116,18 +156,29 @@ k_gemm_skinny(const bf16* __restrict__ X, const bf16* __restrict__ W, int M, int
   for (int e = threadIdx.x; e < MT * 256; e += KS * 64) {
     const int t = e >> 8, ml = (e >> 4) & 15, n = e & 15;
     const int m = t * 16 + ml;
-    if (m >= M) continue;
+    if (m >= M) continue;  // whole 16-lane groups leave together
     float v[NW];
 #pragma unroll
     for (int s = 0; s < NW; ++s) {
       float sum = 0.f;
 #pragma unroll
       for (int w = 0; w < KS; ++w) sum += red[(((w * NW + s) * MT + t) * 16 + ml) * 16 + n];
+      if constexpr (NORM) sum *= sm_inv[m];
       v[s] = sum;
     }
     const size_t o = (size_t)m * N + n0 + n;
     if constexpr (EPI == EPI_STORE) ((bf16*)outv)[o] = (bf16)v[0];
-    else if constexpr (EPI == EPI_RESID) resid[o] += v[0];
+    else if constexpr (EPI == EPI_RESID) {
+      const float xn = resid[o] + v[0];
+      resid[o] = xn;
+      if (fu.xb_out) {
+        fu.xb_out[o] = (bf16)xn;
+        float ss = xn * xn;  // sum over the 16 columns of this tile, fixed butterfly
+#pragma unroll
+        for (int off = 8; off; off >>= 1) ss += __shfl_xor(ss, off);
+        if (n == 0) fu.ss_out[(size_t)m * (N >> 4) + blockIdx.x] = ss;
+      }
+    }
     else if constexpr (EPI == EPI_SWIGLU) ((bf16*)outv)[o] = (bf16)(silu_f(v[0]) * v[NW - 1]);
     else ((float*)outv)[o] = v[0];
   }
@@ -136,42 +187,55 @@ k_gemm_skinny(const bf16* __restrict__ X, const bf16* __restrict__ W, int M, int
 #ifndef LS_SKINNY_PF
 #define LS_SKINNY_PF 0
 #endif
-template <int MT, int EPI, int KS>
-void launch_k(const void* X, const void* W, int M, int N, int K, void* out, float* resid, hipStream_t st) {
+template <int MT, int EPI, int KS, bool NORM>
+void launch_kn(const void* X, const void* W, int M, int N, int K, void* out, float* resid, const SkinnyFusion& fu,
+               hipStream_t st) {
   constexpr int NW = (EPI == EPI_SWIGLU) ? 2 : 1;
-  constexpr int scratch = KS * NW * 4096, red = KS * NW * MT * 1024;
-  constexpr int smem = scratch > red ? scratch : red;
   // register ring depth in 128-wide K blocks
   constexpr int PF = LS_SKINNY_PF ? LS_SKINNY_PF : ((NW * 4 + MT * 4 <= 8 && KS < 16) ? 4 : 2);
-  static bool attr_set = false;
-  if (!attr_set) {
-    (void)hipFuncSetAttribute((const void*)k_gemm_skinny<MT, EPI, KS, PF>, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
-    attr_set = true;
+  const int gam_bytes = NORM ? KS * (((K / 128 + KS - 1) / KS + 1) * 256) : 0;
+  const int scratch = KS * NW * 4096 + gam_bytes, red = KS * NW * MT * 1024;
+  const int smem = scratch > red ? scratch : red;
+  static int attr_bytes = 0;
+  if (smem > attr_bytes) {
+    (void)hipFuncSetAttribute((const void*)k_gemm_skinny<MT, EPI, KS, PF, NORM>, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    attr_bytes = smem;
   }
-  k_gemm_skinny<MT, EPI, KS, PF><<<N / 16, KS * 64, smem, st>>>((const bf16*)X, (const bf16*)W, M, N, K, out, resid);
+  k_gemm_skinny<MT, EPI, KS, PF, NORM><<<N / 16, KS * 64, smem, st>>>((const bf16*)X, (const bf16*)W, M, N, K, out, resid, fu);
+}
+
+template <int MT, int EPI, int KS>
+void launch_k(const void* X, const void* W, int M, int N, int K, void* out, float* resid, const SkinnyFusion& fu,
+              hipStream_t st) {
+  if constexpr (EPI == EPI_STORE || EPI == EPI_SWIGLU) {
+    if (fu.gamma) { launch_kn<MT, EPI, KS, true>(X, W, M, N, K, out, resid, fu, st); return; }
+  }
+  launch_kn<MT, EPI, KS, false>(X, W, M, N, K, out, resid, fu, st);
 }
 
 template <int MT, int EPI>
-void launch_ks(const void* X, const void* W, int M, int N, int K, void* out, float* resid, int ks, hipStream_t st) {
+void launch_ks(const void* X, const void* W, int M, int N, int K, void* out, float* resid, int ks,
+               const SkinnyFusion& fu, hipStream_t st) {
   if (ks == 0) {
-    // enough wavefronts to fill 256 CUs with several each, but at least two K blocks per wave
-    const int tiles = N / 16, nblk = K / 128;
-    ks = 4;
-    while (ks < 16 && tiles * ks < 4096 && nblk / (ks * 2) >= 2) ks *= 2;
+    // measured with cold weights: 4 waves per workgroup stream best once there are >= 512
+    // workgroups; with fewer (N = 4096: 256 of them) 8 waves keep more bytes in flight per CU
+    ks = (N / 16) >= 512 ? 4 : 8;
+    if (K / 128 < ks) ks = 4;
   }
   // 1024-thread workgroups leave too few registers for wide M or for two weight streams
   if (ks == 16 && (MT > 1 || EPI == EPI_SWIGLU)) ks = 8;
   if (ks == 8 && MT == 4 && EPI == EPI_SWIGLU) ks = 4;
-  if (ks == 4) launch_k<MT, EPI, 4>(X, W, M, N, K, out, resid, st);
-  else if (ks == 8) launch_k<MT, EPI, 8>(X, W, M, N, K, out, resid, st);
-  else if constexpr (MT == 1) launch_k<MT, EPI, 16>(X, W, M, N, K, out, resid, st);
+  if (ks == 4) launch_k<MT, EPI, 4>(X, W, M, N, K, out, resid, fu, st);
+  else if (ks == 8) launch_k<MT, EPI, 8>(X, W, M, N, K, out, resid, fu, st);
+  else if constexpr (MT == 1) launch_k<MT, EPI, 16>(X, W, M, N, K, out, resid, fu, st);
 }
 
 template <int EPI>
-void launch_mt(const void* X, const void* W, int M, int N, int K, void* out, float* resid, int ks, hipStream_t st) {
-  if (M <= 16) launch_ks<1, EPI>(X, W, M, N, K, out, resid, ks, st);
-  else if (M <= 32) launch_ks<2, EPI>(X, W, M, N, K, out, resid, ks, st);
-  else launch_ks<4, EPI>(X, W, M, N, K, out, resid, ks, st);
+void launch_mt(const void* X, const void* W, int M, int N, int K, void* out, float* resid, int ks,
+               const SkinnyFusion& fu, hipStream_t st) {
+  if (M <= 16) launch_ks<1, EPI>(X, W, M, N, K, out, resid, ks, fu, st);
+  else if (M <= 32) launch_ks<2, EPI>(X, W, M, N, K, out, resid, ks, fu, st);
+  else launch_ks<4, EPI>(X, W, M, N, K, out, resid, ks, fu, st);
 }
 
 }  // namespace
@@ -181,12 +245,13 @@ bool gemm_skinny_supported(int M, int N, int K) {
 }
 
 void launch_gemm_skinny(Epilogue epi, const void* X, const void* W, int M, int N, int K, void* out, float* resid,
-                        int ks, hipStream_t st) {
+                        int ks, hipStream_t st, const SkinnyFusion* fusion) {
+  const SkinnyFusion fu = fusion ? *fusion : SkinnyFusion{};
   switch (epi) {
-    case EPI_STORE: launch_mt<EPI_STORE>(X, W, M, N, K, out, resid, ks, st); break;
-    case EPI_RESID: launch_mt<EPI_RESID>(X, W, M, N, K, out, resid, ks, st); break;
-    case EPI_SWIGLU: launch_mt<EPI_SWIGLU>(X, W, M, N, K, out, resid, ks, st); break;
-    case EPI_F32: launch_mt<EPI_F32>(X, W, M, N, K, out, resid, ks, st); break;
+    case EPI_STORE: launch_mt<EPI_STORE>(X, W, M, N, K, out, resid, ks, fu, st); break;
+    case EPI_RESID: launch_mt<EPI_RESID>(X, W, M, N, K, out, resid, ks, fu, st); break;
+    case EPI_SWIGLU: launch_mt<EPI_SWIGLU>(X, W, M, N, K, out, resid, ks, fu, st); break;
+    case EPI_F32: launch_mt<EPI_F32>(X, W, M, N, K, out, resid, ks, fu, st); break;
   }
 }
 

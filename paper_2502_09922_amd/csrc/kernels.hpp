@@ -26,6 +26,13 @@ void launch_row_index_decode(const int32_t* seq_lens, int batch, int max_seq, in
 void launch_seq_lens_set(const int32_t* cu_seqlens, int batch, int32_t* seq_lens, hipStream_t st);
 void launch_seq_lens_inc(int batch, int max_seq, int32_t* seq_lens, hipStream_t st);
 
+// Decode step, fused path: row maps + seq_lens increment + fp32 residual rows + their
+// storage-type copy xb + per-16-column sums of squares ss_part[batch][d/16], one launch.
+// table != nullptr: `in` holds int32 token ids and rows are gathered from the table.
+void launch_decode_prologue(uint32_t dt, const void* table, const void* in, int32_t* seq_lens, int batch, int max_seq,
+                            int d, int vocab, int32_t* row_seq, int32_t* row_pos, int32_t* last_rows, float* x,
+                            void* xb, float* ss_part, hipStream_t st);
+
 void launch_embed(uint32_t dt, const void* table, const int32_t* tok, float* x, int rows, int d,
                   int vocab, hipStream_t st);
 void launch_load_hidden(uint32_t dt, const void* in, float* x, size_t n, hipStream_t st);
@@ -49,9 +56,22 @@ void launch_gemm_mfma(Epilogue epi, const void* A, const void* W, int M, int N, 
 
 // bf16 weight-streaming kernel for decode steps (M <= 64); needs N % 16 == 0, K % 128 == 0.
 // ks = wavefronts that split K inside a workgroup (4, 8, 16), 0 = chosen from the shape.
+// Optional RMSNorm fusion of the decode step (all pointers device memory):
+//   gamma != nullptr (EPI_STORE / EPI_SWIGLU): X is xb = bf16(x), un-normalised; the kernel
+//     multiplies by gamma[K] and by 1/sqrt(sum(ss_in[row][0..n_part)) / K + eps).
+//   xb_out != nullptr (EPI_RESID): also write bf16 of the updated residual rows to xb_out[M,N]
+//     and each row's sum of squares per 16-column tile to ss_out[M][N/16].
+struct SkinnyFusion {
+  const __bf16* gamma = nullptr;
+  const float* ss_in = nullptr;
+  int n_part = 0;
+  float eps = 0.f;
+  __bf16* xb_out = nullptr;
+  float* ss_out = nullptr;
+};
 bool gemm_skinny_supported(int M, int N, int K);
 void launch_gemm_skinny(Epilogue epi, const void* X, const void* W, int M, int N, int K, void* out, float* resid,
-                        int ks, hipStream_t st);
+                        int ks, hipStream_t st, const SkinnyFusion* fusion = nullptr);
 
 // Rotate q (in place inside qkv) and k by the per-position cos/sin table, write k and v
 // into the cache at [seq][kv head][pos].  qkv is [rows, (Hq+2Hkv)*hd].

@@ -42,6 +42,57 @@ __global__ void k_seq_lens_inc(int batch, int max_seq, int32_t* seq_lens) {
   if (b < batch && seq_lens[b] >= 0 && seq_lens[b] < max_seq) seq_lens[b] += 1;
 }
 
+// One decode step's bookkeeping and first-layer inputs in a single launch, one workgroup
+// per sequence: row maps, seq_lens += 1 (a full sequence is left alone and marked -1), the
+// fp32 residual row, its bf16 copy, and the sum of squares of every 16-column tile.
+template <class T>
+__global__ void __launch_bounds__(256) k_decode_prologue(const T* __restrict__ table, const void* __restrict__ in,
+                                                         int32_t* seq_lens, int max_seq, int d, int vocab,
+                                                         int32_t* row_seq, int32_t* row_pos, int32_t* last_rows,
+                                                         float* __restrict__ x, T* __restrict__ xb,
+                                                         float* __restrict__ ss_part) {
+  const int b = blockIdx.x;
+  if (threadIdx.x == 0) {
+    const int p = seq_lens[b];
+    const bool ok = p >= 0 && p < max_seq;
+    row_seq[b] = b;
+    row_pos[b] = ok ? p : -1;
+    last_rows[b] = b;
+    if (ok) seq_lens[b] = p + 1;
+  }
+  const T* src;
+  if (table) {
+    int id = ((const int32_t*)in)[b];
+    id = id < 0 ? 0 : (id >= vocab ? vocab - 1 : id);
+    src = table + (size_t)id * d;
+  } else {
+    src = (const T*)in + (size_t)b * d;
+  }
+  for (int tile = threadIdx.x; tile < (d >> 4); tile += 256) {
+    float ss = 0.f;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+      const T raw = src[tile * 16 + e];
+      const float v = to_f(raw);
+      x[(size_t)b * d + tile * 16 + e] = v;
+      xb[(size_t)b * d + tile * 16 + e] = raw;
+      ss += v * v;
+    }
+    ss_part[(size_t)b * (d >> 4) + tile] = ss;
+  }
+}
+
+void launch_decode_prologue(uint32_t dt, const void* table, const void* in, int32_t* seq_lens, int batch, int max_seq,
+                            int d, int vocab, int32_t* row_seq, int32_t* row_pos, int32_t* last_rows, float* x,
+                            void* xb, float* ss_part, hipStream_t st) {
+  if (dt == F32)
+    k_decode_prologue<float><<<batch, 256, 0, st>>>((const float*)table, in, seq_lens, max_seq, d, vocab, row_seq,
+                                                    row_pos, last_rows, x, (float*)xb, ss_part);
+  else
+    k_decode_prologue<bf16><<<batch, 256, 0, st>>>((const bf16*)table, in, seq_lens, max_seq, d, vocab, row_seq,
+                                                   row_pos, last_rows, x, (bf16*)xb, ss_part);
+}
+
 void launch_row_index_prefill(const int32_t* cu, int batch, int total, int32_t* row_seq,
                               int32_t* row_pos, int32_t* last_rows, hipStream_t st) {
   int n = total > batch ? total : batch;

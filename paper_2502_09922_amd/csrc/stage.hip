@@ -85,7 +85,7 @@ bool span_ok(const ls_cfg* c, int lo, int hi) {
 
 // ---- workspace carving ------------------------------------------------------------------
 struct Carve {
-  size_t cs, x, y, qkv, attn, h, logits, row_seq, row_pos, last_rows, next_tok, total;
+  size_t cs, x, y, qkv, attn, h, logits, row_seq, row_pos, last_rows, next_tok, xb, xb2, ss_a, ss_b, total;
 };
 
 Carve carve(const ls_cfg* c, int lo, int hi) {
@@ -106,6 +106,11 @@ Carve carve(const ls_cfg* c, int lo, int hi) {
   w.row_pos = take(T * sizeof(int32_t));
   w.last_rows = take(B * sizeof(int32_t));
   w.next_tok = take(B * sizeof(int32_t));
+  // decode-step fusion: bf16 copies of the residual rows and per-tile sums of squares
+  w.xb = take(B * d * e);
+  w.xb2 = take(B * d * e);
+  w.ss_a = take(B * ((d + 15) / 16) * sizeof(float));
+  w.ss_b = take(B * ((d + 15) / 16) * sizeof(float));
   (void)lo;
   w.total = off;
   return w;
@@ -375,6 +380,7 @@ ls_status forward(ls_stage* s, bool prefill, const void* in, const int32_t* cu_d
   int32_t* last_rows = (int32_t*)(ws + s->w.last_rows);
   const bool timed = s->profiling && prefill;
   const bool probing = s->probe_op != LS_OP_NONE && s->probe_phase == (prefill ? 0 : 1) && !s->probe_a.empty();
+
   // PROBE(op, launch): bracket the launch with an event pair if this (op, layer) is probed
 #define PROBE(op, launch)                                                        \
   do {                                                                           \
@@ -387,6 +393,61 @@ ls_status forward(ls_stage* s, bool prefill, const void* in, const int32_t* cu_d
       s->probe_count++;                                                          \
     }                                                                            \
   } while (0)
+  const size_t kv_layer = (size_t)c.max_batch * hkv * c.max_seq * hd * e;
+
+  // ---- decode step with the RMSNorms folded into the weight-streaming GEMMs
+  const bool fused = !prefill && dt == BF16 && d % 16 == 0 && attn_decode_supported(hq, hkv, hd) &&
+                     gemm_skinny_supported(rows, qkv_cols, d) && gemm_skinny_supported(rows, d, hq * hd) &&
+                     gemm_skinny_supported(rows, F, d) && gemm_skinny_supported(rows, d, F);
+  if (fused) {
+    __bf16* xb = (__bf16*)(ws + s->w.xb);
+    __bf16* xb2 = (__bf16*)(ws + s->w.xb2);
+    float* ss_a = (float*)(ws + s->w.ss_a);
+    float* ss_b = (float*)(ws + s->w.ss_b);
+    const void* table = nullptr;
+    if (s->first) {
+      const Block* eb = s->find(LS_BLOCK_EMBED);
+      LS_HIP(hipStreamWaitEvent(st, eb->loaded, 0));
+      table = s->slab + eb->off;
+    }
+    launch_decode_prologue(dt, table, in, kv->seq_lens, batch, c.max_seq, d, c.vocab, row_seq, row_pos, last_rows, x,
+                           xb, ss_a, st);
+    const int n_layers = s->hi - s->lo;
+    for (int li = 0; li < n_layers; ++li) {
+      const Block& b = s->blocks[s->layer0 + li];
+      TensorSpan sp[6];
+      block_tensors(&c, b.layer, sp, nullptr);
+      const char* base = s->slab + b.off;
+      LS_HIP(hipStreamWaitEvent(st, b.loaded, 0));  // the gate
+      char* kc = (char*)kv->k + li * kv_layer;
+      char* vc = (char*)kv->v + li * kv_layer;
+      SkinnyFusion f_qkv, f_o, f_gu, f_dn;
+      f_qkv.gamma = (const __bf16*)(base + sp[0].off); f_qkv.ss_in = ss_a; f_qkv.n_part = d / 16; f_qkv.eps = c.rms_eps;
+      f_o.xb_out = xb2; f_o.ss_out = ss_b;
+      f_gu.gamma = (const __bf16*)(base + sp[3].off); f_gu.ss_in = ss_b; f_gu.n_part = d / 16; f_gu.eps = c.rms_eps;
+      // the last layer of a middle stage writes the stage output directly
+      f_dn.xb_out = (li == n_layers - 1 && !s->last) ? (__bf16*)out : xb; f_dn.ss_out = ss_a;
+      PROBE(LS_OP_GEMM_QKV, launch_gemm_skinny(EPI_STORE, xb, base + sp[1].off, rows, qkv_cols, d, qkv, nullptr, 0, st, &f_qkv));
+      PROBE(LS_OP_ATTENTION, launch_attention_block(dt, nullptr, batch, 1, qkv, cs, kc, vc, row_seq, row_pos, rows, hq,
+                                                    hkv, hd, c.max_seq, attn, st));
+      PROBE(LS_OP_GEMM_O, launch_gemm_skinny(EPI_RESID, attn, base + sp[2].off, rows, d, hq * hd, nullptr, x, 0, st, &f_o));
+      PROBE(LS_OP_GEMM_GATEUP, launch_gemm_skinny(EPI_SWIGLU, xb2, base + sp[4].off, rows, F, d, hbuf, nullptr, 0, st, &f_gu));
+      PROBE(LS_OP_GEMM_DOWN, launch_gemm_skinny(EPI_RESID, hbuf, base + sp[5].off, rows, d, F, nullptr, x, 0, st, &f_dn));
+    }
+    if (s->last) {
+      const Block* hb = s->find(s->hi);
+      TensorSpan sp[6];
+      block_tensors(&c, hb->layer, sp, nullptr);
+      const char* base = s->slab + hb->off;
+      LS_HIP(hipStreamWaitEvent(st, hb->loaded, 0));
+      float* logits = logits_out ? logits_out : (float*)(ws + s->w.logits);
+      launch_rmsnorm(dt, x, base + sp[0].off, y, batch, d, c.rms_eps, last_rows, st);
+      launch_gemm(dt, EPI_F32, y, base + sp[1].off, batch, c.vocab, d, logits, nullptr, st);
+      launch_argmax(logits, batch, c.vocab, (int32_t*)out, st);
+    }
+    LS_HIP(hipGetLastError());
+    return LS_OK;
+  }
 
   if (prefill) launch_row_index_prefill(cu_dev, batch, rows, row_seq, row_pos, last_rows, st);
   else launch_row_index_decode(kv->seq_lens, batch, c.max_seq, row_seq, row_pos, last_rows, st);
@@ -399,7 +460,6 @@ ls_status forward(ls_stage* s, bool prefill, const void* in, const int32_t* cu_d
     launch_load_hidden(dt, in, x, (size_t)rows * d, st);
   }
 
-  const size_t kv_layer = (size_t)c.max_batch * hkv * c.max_seq * hd * e;
   for (int li = 0; li < s->hi - s->lo; ++li) {
     const Block& b = s->blocks[s->layer0 + li];
     TensorSpan sp[6];
