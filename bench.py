@@ -160,6 +160,17 @@ def execute_while_load(args, synth, st, blocks, shape, batch, prompt, dsteps):
     print(json.dumps(out))
 
 
+def recorded_traffic(workload):
+    """HBM bytes per launch of the dominant kernel as measured by the rocprofv3 --pmc runs
+    whose summary is committed under profiles/ (a profiler cannot run inside this script)."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    try:
+        with open(path) as f:
+            return json.load(f).get(workload, {}).get("decode_gateup_gemm_bytes_per_launch")
+    except (OSError, ValueError):
+        return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -167,6 +178,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--workload", default="llama7b_stage_l8_16_b8_s512_d128", choices=sorted(WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run one plain 1 GiB device copy (calibrates rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1")
@@ -190,6 +203,13 @@ def main():
     for layer in st.block_ids():
         st.load_block(layer, blocks[layer], stream=stream)
     torch.cuda.synchronize()
+
+    if args.copy_probe:
+        src = torch.ones(1 << 30, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     T = batch * prompt
     if st.first:
@@ -291,7 +311,8 @@ def main():
                    "gbytes_per_s": dec_bytes / (t_dec * 1e-3) / 1e9,
                    "frac_of_hbm_peak": dec_bytes / (t_dec * 1e-3) / 1e9 / HBM_PEAK_GBS},
         "roofline": {"kernel": "decode gate-up GEMM + SwiGLU", "bound": "hbm", "achieved": achieved,
-                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": recorded_traffic(args.workload),
                      "bytes_per_launch": gu_bytes, "avg_ms": gu_ms, "launches_timed": len(probe_dec)},
         "roofline_prefill": {"kernel": "prefill gate-up GEMM + SwiGLU", "bound": "mfma", "achieved": pg_tf,
                              "peak": MFMA_BF16_PEAK_TF, "unit": "TFLOP/s", "frac": pg_tf / MFMA_BF16_PEAK_TF,

@@ -29,8 +29,11 @@ namespace ls {
 
 namespace {
 
+#ifndef LS_SKINNY_MINWG
+#define LS_SKINNY_MINWG 1
+#endif
 template <int MT, int EPI, int KS, int PF, bool NORM>
-__global__ void __launch_bounds__(KS * 64)
+__global__ void __launch_bounds__(KS * 64, LS_SKINNY_MINWG)
 k_gemm_skinny(const bf16* __restrict__ X, const bf16* __restrict__ W, int M, int N, int K,
               void* __restrict__ outv, float* __restrict__ resid, SkinnyFusion fu) {
   constexpr bool GLU = (EPI == EPI_SWIGLU);
@@ -191,8 +194,9 @@ template <int MT, int EPI, int KS, bool NORM>
 void launch_kn(const void* X, const void* W, int M, int N, int K, void* out, float* resid, const SkinnyFusion& fu,
                hipStream_t st) {
   constexpr int NW = (EPI == EPI_SWIGLU) ? 2 : 1;
-  // register ring depth in 128-wide K blocks
-  constexpr int PF = LS_SKINNY_PF ? LS_SKINNY_PF : ((NW * 4 + MT * 4 <= 8 && KS < 16) ? 4 : 2);
+  // register ring depth in 128-wide K blocks; two blocks measured best for every shape
+  // (a deeper ring costs registers, hence resident wavefronts)
+  constexpr int PF = LS_SKINNY_PF ? LS_SKINNY_PF : 2;
   const int gam_bytes = NORM ? KS * (((K / 128 + KS - 1) / KS + 1) * 256) : 0;
   const int scratch = KS * NW * 4096 + gam_bytes, red = KS * NW * MT * 1024;
   const int smem = scratch > red ? scratch : red;
