@@ -2,9 +2,12 @@
 //
 // One 512-thread workgroup (8 wavefronts, 2 x 4) owns a 256 x 256 tile of C and walks K in
 // steps of 64.  Both operands are K-contiguous, so a lane's 16-byte global load is exactly
-// the 8-element K slice an MFMA operand wants.  Tiles are staged in LDS (double buffered,
-// 128 KB), 16-byte chunks XOR-swizzled by row so that the 32 rows an MFMA operand read
-// touches fall into different banks.  v_mfma_f32_32x32x16_bf16: the activation tile is the
+// the 8-element K slice an MFMA operand wants.  Tiles go from global memory straight into
+// LDS (global_load_lds_dwordx4: no staging registers, no LDS store instructions), double
+// buffered (128 KB).  One such instruction fills 1 KB = 8 tile rows of 128 bytes; 16-byte
+// chunks are XOR-swizzled by (row/2)&7 -- the lane that fills physical chunk p of row r
+// fetches logical chunk p ^ ((r/2)&7) -- so that the 16 rows a quarter-wave reads for an MFMA
+// operand fall into different banks (LDS has 64 banks here).  v_mfma_f32_32x32x16_bf16: the activation tile is the
 // A operand (rows m), the weight tile the B operand (columns n); in the result a lane holds
 // column n = lane%32 and rows 8*(r/4) + 4*(lane/32) + r%4, r = 0..15.
 //
@@ -52,28 +55,28 @@ k_gemm_mfma(const bf16* __restrict__ A, const bf16* __restrict__ W, int M, int N
   const int m0 = tm * BM;
   const int n0 = GLU ? tn * (BN / 2) : tn * BN;  // GLU: 128 output columns per tile
 
-  // ---- global -> register staging: thread owns chunk c of rows r0 + 64 i
-  const int c = tid & 7, r0 = tid >> 3;
+  // ---- global -> LDS: wave w fills tile rows 32w..32w+31 of both operands, 8 rows per
+  // instruction; lane l supplies row 32w + 8i + l/8, physical chunk l%8
   const bf16* ap[4];
   const bf16* wp[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    int row = r0 + 64 * i;
-    int am = min(m0 + row, M - 1);
+    const int row = wave * 32 + i * 8 + (lane >> 3);
+    const int c = (lane & 7) ^ ((row >> 1) & 7);
+    const int am = min(m0 + row, M - 1);
     ap[i] = A + (size_t)am * K + c * 8;
     int wrow;
     if constexpr (GLU) {
       // tile row -> weight row: 32-row blocks alternate gate / up, so that a wave's two
       // column tiles are the gate and the up projection of the same 32 output columns
-      int blk = row >> 5;
-      int f = min(n0 + (blk >> 1) * 32 + (row & 31), N - 1);
+      const int blk = row >> 5;
+      const int f = min(n0 + (blk >> 1) * 32 + (row & 31), N - 1);
       wrow = (blk & 1) * N + f;
     } else {
       wrow = min(n0 + row, N - 1);
     }
     wp[i] = W + (size_t)wrow * K + c * 8;
   }
-  u32x4 ra[4], rw[4];
   f32x16 acc[4][2];
 #pragma unroll
   for (int i = 0; i < 4; ++i)
@@ -84,10 +87,8 @@ k_gemm_mfma(const bf16* __restrict__ A, const bf16* __restrict__ W, int M, int N
 
   const int lr = lane & 31, lh = lane >> 5;
   const int KT = K / BK;
-  // LDS byte offsets of this thread's staging chunks and of its operand reads
-  int st_off[4], a_off[4][4], b_off[4][2];
-#pragma unroll
-  for (int i = 0; i < 4; ++i) st_off[i] = swz(r0 + 64 * i, c);
+  // LDS byte offsets of this lane's operand reads
+  int a_off[4][4], b_off[4][2];
 #pragma unroll
   for (int kk = 0; kk < 4; ++kk) {
 #pragma unroll
@@ -95,46 +96,63 @@ k_gemm_mfma(const bf16* __restrict__ A, const bf16* __restrict__ W, int M, int N
 #pragma unroll
     for (int j = 0; j < 2; ++j) b_off[kk][j] = TILE_BYTES + swz(wn * 64 + j * 32 + lr, kk * 2 + lh);
   }
+  typedef __attribute__((address_space(3))) void lds_void;
+  const int fill_off = (wave * 32) * 128;  // this wave's first row inside an operand tile
 
-#define LS_LOAD_TILE(k0)                                              \
-  _Pragma("unroll") for (int i = 0; i < 4; ++i) {                     \
-    ra[i] = *reinterpret_cast<const u32x4*>(ap[i] + (k0));            \
-    rw[i] = *reinterpret_cast<const u32x4*>(wp[i] + (k0));            \
+#define LS_FILL_TILE(buf, k0)                                                                          \
+  _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                                      \
+    __builtin_amdgcn_global_load_lds((const void*)(ap[i] + (k0)),                                      \
+        (lds_void*)(smem + (buf) * 2 * TILE_BYTES + fill_off + i * 1024), 16, 0, 0);                   \
+    __builtin_amdgcn_global_load_lds((const void*)(wp[i] + (k0)),                                      \
+        (lds_void*)(smem + (buf) * 2 * TILE_BYTES + TILE_BYTES + fill_off + i * 1024), 16, 0, 0);      \
   }
-#define LS_STORE_TILE(buf)                                                                   \
-  _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                            \
-    *reinterpret_cast<u32x4*>(smem + (buf) * 2 * TILE_BYTES + st_off[i]) = ra[i];            \
-    *reinterpret_cast<u32x4*>(smem + (buf) * 2 * TILE_BYTES + TILE_BYTES + st_off[i]) = rw[i]; \
+  // operand fragments are double buffered in registers: the LDS reads of k-step kk+1 are
+  // issued before the MFMAs of k-step kk, so the matrix pipe does not wait on LDS latency
+#define LS_READ_FRAGS(buf, kk, set)                                                                \
+  {                                                                                                \
+    _Pragma("unroll") for (int i = 0; i < 4; ++i)                                                  \
+      af[set][i] = *reinterpret_cast<const bf16x8*>(smem + (buf) * 2 * TILE_BYTES + a_off[kk][i]); \
+    _Pragma("unroll") for (int j = 0; j < 2; ++j)                                                  \
+      bfr[set][j] = *reinterpret_cast<const bf16x8*>(smem + (buf) * 2 * TILE_BYTES + b_off[kk][j]); \
   }
-#define LS_COMPUTE_TILE(buf)                                                                     \
-  _Pragma("unroll") for (int kk = 0; kk < 4; ++kk) {                                             \
-    bf16x8 af[4], bfr[2];                                                                        \
-    _Pragma("unroll") for (int i = 0; i < 4; ++i)                                                \
-      af[i] = *reinterpret_cast<const bf16x8*>(smem + (buf) * 2 * TILE_BYTES + a_off[kk][i]);    \
-    _Pragma("unroll") for (int j = 0; j < 2; ++j)                                                \
-      bfr[j] = *reinterpret_cast<const bf16x8*>(smem + (buf) * 2 * TILE_BYTES + b_off[kk][j]);   \
-    _Pragma("unroll") for (int i = 0; i < 4; ++i)                                                \
-      _Pragma("unroll") for (int j = 0; j < 2; ++j)                                              \
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);  \
+#define LS_MFMA_STEP(set)                                                                          \
+  _Pragma("unroll") for (int i = 0; i < 4; ++i)                                                    \
+    _Pragma("unroll") for (int j = 0; j < 2; ++j)                                                  \
+      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[set][i], bfr[set][j], acc[i][j], 0, 0, 0);
+#define LS_COMPUTE_TILE(buf)                                    \
+  {                                                             \
+    bf16x8 af[2][4], bfr[2][2];                                 \
+    LS_READ_FRAGS(buf, 0, 0)                                    \
+    LS_READ_FRAGS(buf, 1, 1)                                    \
+    LS_MFMA_STEP(0)                                             \
+    __builtin_amdgcn_sched_barrier(0);                          \
+    LS_READ_FRAGS(buf, 2, 0)                                    \
+    LS_MFMA_STEP(1)                                             \
+    __builtin_amdgcn_sched_barrier(0);                          \
+    LS_READ_FRAGS(buf, 3, 1)                                    \
+    LS_MFMA_STEP(0)                                             \
+    __builtin_amdgcn_sched_barrier(0);                          \
+    LS_MFMA_STEP(1)                                             \
   }
+  // s_waitcnt vmcnt(0): the fills this wave issued have landed in LDS
+#define LS_WAIT_FILLS() __builtin_amdgcn_s_waitcnt(0x0F70)
 
-  LS_LOAD_TILE(0)
-  LS_STORE_TILE(0)
+  LS_FILL_TILE(0, 0)
+  LS_WAIT_FILLS();
   __syncthreads();
-  for (int kt = 0; kt + 1 < KT; ++kt) {
+  for (int kt = 0; kt < KT; ++kt) {
     const int buf = kt & 1;
-    LS_LOAD_TILE((kt + 1) * BK)
+    // the other buffer was last read in step kt-1, which every wave has left (barrier)
+    if (kt + 1 < KT) LS_FILL_TILE(buf ^ 1, (kt + 1) * BK)
     LS_COMPUTE_TILE(buf)
-    LS_STORE_TILE(buf ^ 1)
+    LS_WAIT_FILLS();
     __syncthreads();
   }
-  {
-    const int buf = (KT - 1) & 1;
-    LS_COMPUTE_TILE(buf)
-  }
-#undef LS_LOAD_TILE
-#undef LS_STORE_TILE
+#undef LS_FILL_TILE
 #undef LS_COMPUTE_TILE
+#undef LS_READ_FRAGS
+#undef LS_MFMA_STEP
+#undef LS_WAIT_FILLS
 
   // ---- epilogue
 #pragma unroll
