@@ -64,26 +64,27 @@ def st_block_bytes(st, layer):
     return b.ls_stage_block_bytes(st.handle, layer)
 
 
-def cpu_baseline(synth, shape, lo, batch, prompt, dsteps):
+def cpu_baseline(synth, shape, lo, hi, batch, prompt, dsteps):
     """The oracle as it stands, timed on this machine's host cores on a bounded sample of the
-    same workload: ONE layer at the real dimensions, the full batch and prompt length and 8
-    decode steps; scaled linearly in layers to the stage (extrapolated)."""
+    same workload: up to 8 layers of the stage at the real dimensions, the full batch and
+    prompt length, and 8 decode steps; scaled linearly in layers if the stage has more."""
     from oracle.stage_oracle import OracleStage
 
     import threadpoolctl
 
-    n_prompt, n_dec = prompt, min(8, dsteps)
+    n_layers, n_dec = min(hi - lo, 8), min(8, dsteps)
     one = shape.with_(vocab=0)
-    ora = OracleStage(one, lo, lo + 1, batch, n_prompt + n_dec)
-    ora.load_tensors(lo, synth.layer_tensors(one, SEED, lo))
-    x = synth.hidden_states(one, SEED + 1, batch * n_prompt)
+    ora = OracleStage(one, lo, lo + n_layers, batch, prompt + n_dec)
+    for l in range(lo, lo + n_layers):
+        ora.load_tensors(l, synth.layer_tensors(one, SEED, l))
+    x = synth.hidden_states(one, SEED + 1, batch * prompt)
     t0 = time.perf_counter()
-    ora.prefill(x, [n_prompt] * batch)
+    ora.prefill(x, [prompt] * batch)
     for t in range(n_dec):
         ora.decode(synth.hidden_states(one, SEED + 2 + t, batch))
     dt = time.perf_counter() - t0
     threads = max([p["num_threads"] for p in threadpoolctl.threadpool_info()] or [1])
-    return dt, batch * (n_prompt + n_dec), threads, n_prompt, n_dec
+    return dt, batch * (prompt + n_dec), threads, n_layers, n_dec
 
 
 def execute_while_load(args, synth, st, blocks, shape, batch, prompt, dsteps):
@@ -319,11 +320,12 @@ def main():
                              "flops_per_launch": pg_flops, "avg_ms": pg_ms, "launches_timed": len(probe_pre)},
     }
     if not args.no_cpu_baseline:
-        dt, ntok, threads, n_prompt, n_dec = cpu_baseline(synth, shape, lo, batch, prompt, dsteps)
+        dt, ntok, threads, n_layers, n_dec = cpu_baseline(synth, shape, lo, hi, batch, prompt, dsteps)
         res["cpu_baseline"] = {
-            "value": ntok / (dt * L), "unit": "tokens/s", "cores": threads, "kind": "oracle",
-            "sample": "1 of %d layers at real dims, %d seqs x (%d prompt + %d decode) tokens in %.1f s; "
-                      "scaled linearly to %d layers (extrapolated)" % (L, batch, n_prompt, n_dec, dt, L),
+            "value": ntok / (dt * L / n_layers), "unit": "tokens/s", "cores": threads, "kind": "oracle",
+            "sample": "%d of %d layers at real dims, %d seqs x (%d prompt + %d decode) tokens in %.1f s%s"
+                      % (n_layers, L, batch, prompt, n_dec, dt,
+                         "" if n_layers == L else "; scaled linearly to %d layers (extrapolated)" % L),
         }
     st.close()
     print(json.dumps(res))
