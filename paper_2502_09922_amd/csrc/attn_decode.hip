@@ -23,7 +23,13 @@ namespace ls {
 
 namespace {
 
-constexpr int NW = 8;  // wavefronts per workgroup = context splits
+#ifndef LS_ATTN_NW
+#define LS_ATTN_NW 8
+#endif
+#ifndef LS_ATTN_U
+#define LS_ATTN_U 4
+#endif
+constexpr int NW = LS_ATTN_NW;  // wavefronts per workgroup = context splits
 
 template <int HD, int G>
 __global__ void __launch_bounds__(NW * 64)
@@ -32,7 +38,7 @@ k_attn_decode(const bf16* __restrict__ qkv, int qkv_stride, const float2* __rest
               const int32_t* __restrict__ row_pos, int hq, int hkv, int max_seq, bf16* __restrict__ out) {
   constexpr int LPK = HD / 8;     // lanes per key
   constexpr int KPI = 64 / LPK;   // keys per load instruction
-  constexpr int U = 4;            // load instructions in flight per operand
+  constexpr int U = (G >= 4) ? 2 : LS_ATTN_U;  // load instructions in flight per operand
   __shared__ float sm_m[NW][G], sm_l[NW][G];
   __shared__ float sm_acc[NW][G][HD];
   const int r = blockIdx.x, kh = blockIdx.y;
