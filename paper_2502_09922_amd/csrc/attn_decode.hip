@@ -27,7 +27,7 @@ namespace {
 #define LS_ATTN_NW 8
 #endif
 #ifndef LS_ATTN_U
-#define LS_ATTN_U 4
+#define LS_ATTN_U 2
 #endif
 constexpr int NW = LS_ATTN_NW;  // wavefronts per workgroup = context splits
 
@@ -100,23 +100,42 @@ k_attn_decode(const bf16* __restrict__ qkv, int qkv_stride, const float2* __rest
     m[g] = mn_;                                                                              \
   }
 
-  for (int j0 = k_begin; j0 < k_end; j0 += KPI * U) {
-    bf16x8 kf[U], vf[U];
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int key = min(j0 + u * KPI + slot, ctx - 1);  // clamped: always a valid cache row
-      kf[u] = *reinterpret_cast<const bf16x8*>(kb + (size_t)key * HD + dl * 8);
-      vf[u] = *reinterpret_cast<const bf16x8*>(vb + (size_t)key * HD + dl * 8);
-    }
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const bool valid = (j0 + u * KPI + slot) < k_end;
-      float kx[8], vx[8];
-#pragma unroll
-      for (int e = 0; e < 8; ++e) { kx[e] = (float)kf[u][e]; vx[e] = (float)vf[u][e]; }
-      LS_KEY_UPDATE(kx, vx, valid)
+  // the cache stream is software pipelined: the loads of the next group of U*KPI keys are
+  // in flight while the current group is folded into the softmax state; a load whose keys
+  // all lie past the wave's range is not issued at all
+#define LS_LOAD_GROUP(buf, j0_)                                                               \
+  _Pragma("unroll") for (int u = 0; u < U; ++u) {                                             \
+    if ((j0_) + u * KPI < k_end) {                                                            \
+      const int key_ = min((j0_) + u * KPI + slot, ctx - 1); /* clamped: a valid cache row */ \
+      kf[buf][u] = *reinterpret_cast<const bf16x8*>(kb + (size_t)key_ * HD + dl * 8);         \
+      vf[buf][u] = *reinterpret_cast<const bf16x8*>(vb + (size_t)key_ * HD + dl * 8);         \
+    }                                                                                         \
+  }
+#define LS_FOLD_GROUP(buf, j0_)                                                               \
+  _Pragma("unroll") for (int u = 0; u < U; ++u) {                                             \
+    if ((j0_) + u * KPI < k_end) {                                                            \
+      const bool valid = ((j0_) + u * KPI + slot) < k_end;                                    \
+      float kx[8], vx[8];                                                                     \
+      _Pragma("unroll") for (int e = 0; e < 8; ++e) {                                         \
+        kx[e] = (float)kf[buf][u][e];                                                         \
+        vx[e] = (float)vf[buf][u][e];                                                         \
+      }                                                                                       \
+      LS_KEY_UPDATE(kx, vx, valid)                                                            \
+    }                                                                                         \
+  }
+  {
+    constexpr int STEP = KPI * U;
+    bf16x8 kf[2][U], vf[2][U];
+    LS_LOAD_GROUP(0, k_begin)
+    for (int j0 = k_begin; j0 < k_end; j0 += 2 * STEP) {
+      LS_LOAD_GROUP(1, j0 + STEP)
+      LS_FOLD_GROUP(0, j0)
+      LS_LOAD_GROUP(0, j0 + 2 * STEP)
+      LS_FOLD_GROUP(1, j0 + STEP)
     }
   }
+#undef LS_LOAD_GROUP
+#undef LS_FOLD_GROUP
 
   // the new row: rotate k, round both to bf16, append to the cache, attend to it
   if (wave == 0) {

@@ -343,6 +343,43 @@ __global__ void __launch_bounds__(256) k_rope_append(T* __restrict__ qkv, const 
   }
 }
 
+// bf16 fast path (head_dim % 8 == 0): a thread owns 8 consecutive elements (4 pairs) of one
+// head of one row: one 16-byte load, two 16-byte table loads, one 16-byte store.
+__global__ void __launch_bounds__(256) k_rope_append_vec(bf16* __restrict__ qkv, const float* __restrict__ cs,
+                                                         const int32_t* __restrict__ row_seq,
+                                                         const int32_t* __restrict__ row_pos, int hq, int hkv,
+                                                         int hd, int max_seq, bf16* __restrict__ kc,
+                                                         bf16* __restrict__ vc) {
+  const int r = blockIdx.x;
+  const int pos = row_pos[r];
+  if (pos < 0) return;
+  const int cpr = hd >> 3;                       // 16-byte chunks per head
+  const int item = blockIdx.y * 256 + threadIdx.x;
+  if (item >= (hq + 2 * hkv) * cpr) return;
+  const int head = item / cpr, ch = item - head * cpr;
+  bf16* src = qkv + (size_t)r * (hq + 2 * hkv) * hd + (size_t)head * hd + ch * 8;
+  bf16x8 v = *reinterpret_cast<const bf16x8*>(src);
+  if (head < hq + hkv) {
+    const f32x4* t = reinterpret_cast<const f32x4*>(cs + ((size_t)pos * (hd >> 1) + ch * 4) * 2);
+    const f32x4 t0 = t[0], t1 = t[1];  // (cos, sin) of pairs 0,1 and 2,3
+    const float c[4] = {t0[0], t0[2], t1[0], t1[2]}, sn[4] = {t0[1], t0[3], t1[1], t1[3]};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const float u0 = (float)v[2 * i], u1 = (float)v[2 * i + 1];
+      v[2 * i] = (bf16)(u0 * c[i] - u1 * sn[i]);
+      v[2 * i + 1] = (bf16)(u0 * sn[i] + u1 * c[i]);
+    }
+  }
+  if (head < hq) {
+    *reinterpret_cast<bf16x8*>(src) = v;
+  } else {
+    const bool isv = head >= hq + hkv;
+    const int kh = isv ? head - hq - hkv : head - hq;
+    const size_t o = (((size_t)row_seq[r] * hkv + kh) * max_seq + pos) * hd + ch * 8;
+    *reinterpret_cast<bf16x8*>((isv ? vc : kc) + o) = v;
+  }
+}
+
 void launch_rope_append(uint32_t dt, void* qkv, const float* cs_table, const int32_t* row_seq,
                         const int32_t* row_pos, int rows, int hq, int hkv, int hd, int max_seq,
                         void* kcache, void* vcache, hipStream_t st) {
@@ -350,7 +387,11 @@ void launch_rope_append(uint32_t dt, void* qkv, const float* cs_table, const int
   if (dt == F32)
     k_rope_append<float><<<rows, 256, 0, st>>>((float*)qkv, (const float2*)cs_table, row_seq, row_pos, hq, hkv,
                                                hd, max_seq, (float*)kcache, (float*)vcache);
-  else
+  else if (hd % 8 == 0) {
+    dim3 grid(rows, ((hq + 2 * hkv) * (hd / 8) + 255) / 256);
+    k_rope_append_vec<<<grid, 256, 0, st>>>((bf16*)qkv, cs_table, row_seq, row_pos, hq, hkv, hd, max_seq,
+                                            (bf16*)kcache, (bf16*)vcache);
+  } else
     k_rope_append<bf16><<<rows, 256, 0, st>>>((bf16*)qkv, (const float2*)cs_table, row_seq, row_pos, hq, hkv,
                                               hd, max_seq, (bf16*)kcache, (bf16*)vcache);
 }
