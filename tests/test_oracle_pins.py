@@ -418,3 +418,20 @@ def test_planted_mistakes_are_caught(monkeypatch):
             m.setattr(so, name, bad)
             with pytest.raises(AssertionError):
                 _run_pins()
+
+
+def test_tiny_fp32_golden_is_reproduced():
+    """The stored oracle output for benchmark config 1 (tests/golden/, written by the
+    committed script from the oracle alone) is what the oracle computes today."""
+    import importlib.util
+    import os
+
+    here = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+    spec = importlib.util.spec_from_file_location("make_golden", os.path.join(here, "make_tiny_fp32_golden.py"))
+    mod = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mod)
+    prompt, toks, tops = mod.compute()
+    rows = dict(l.split(" ", 1) for l in open(os.path.join(here, "tiny_fp32_greedy.txt")) if not l.startswith("#"))
+    assert list(map(int, rows["prompt"].split())) == prompt
+    assert list(map(int, rows["greedy"].split())) == toks
+    np.testing.assert_allclose(list(map(float, rows["top_logit"].split())), tops, rtol=1e-9)
