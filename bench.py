@@ -29,6 +29,9 @@ WORKLOADS = {
     # name: (shape key, layer_lo, layer_hi, batch, prompt, decode steps)
     "llama7b_stage_l8_16_b8_s512_d128": ("llama7b", 8, 16, 8, 512, 128),
     "tiny_f32_b1_s32_d8": ("tiny_f32", 0, 2, 1, 32, 8),
+    # slices of the larger benchmark configurations (fewer layers, same per-layer shapes)
+    "llama13b_l4_b32_s1024_d16": ("llama13b", 16, 20, 32, 1024, 16),
+    "llama70b_l4_b64_ragged128_2048_d16": ("llama70b", 40, 44, 64, (128, 2048), 16),
     # execute-while-load: the whole 7B-shaped model streams in as 34 blocks while prefill runs
     "ewl_llama7b_full_b16_s512_d32": ("llama7b", 0, 32, 16, 512, 32),
     # same model, a prompt batch heavy enough that compute, not the host link, is the longer leg
@@ -37,10 +40,17 @@ WORKLOADS = {
 SEED = 1234
 
 
-def build_stage(synth, Stage, pack_block, shape, lo, hi, batch, prompt, steps):
+def prompt_lengths(synth, batch, prompt):
+    """Uniform prompts, or (lo, hi): seeded ragged lengths uniform on [lo, hi]."""
+    if isinstance(prompt, tuple):
+        return [int(n) for n in synth.ragged_lengths(SEED + 7, batch, prompt[0], prompt[1])]
+    return [prompt] * batch
+
+
+def build_stage(synth, Stage, pack_block, shape, lo, hi, lengths, steps):
     import torch
 
-    st = Stage(shape, lo, hi, batch, prompt + steps, batch * prompt)
+    st = Stage(shape, lo, hi, len(lengths), max(lengths) + steps, sum(lengths))
 
     def make(layer):
         if layer == -1:
@@ -64,7 +74,7 @@ def st_block_bytes(st, layer):
     return b.ls_stage_block_bytes(st.handle, layer)
 
 
-def cpu_baseline(synth, shape, lo, hi, batch, prompt, dsteps):
+def cpu_baseline(synth, shape, lo, hi, lengths, dsteps):
     """The oracle as it stands, timed on this machine's host cores on a bounded sample of the
     same workload: up to 8 layers of the stage at the real dimensions, the full batch and
     prompt length, and 8 decode steps; scaled linearly in layers if the stage has more."""
@@ -73,18 +83,19 @@ def cpu_baseline(synth, shape, lo, hi, batch, prompt, dsteps):
     import threadpoolctl
 
     n_layers, n_dec = min(hi - lo, 8), min(8, dsteps)
+    batch, prompt = len(lengths), max(lengths)
     one = shape.with_(vocab=0)
     ora = OracleStage(one, lo, lo + n_layers, batch, prompt + n_dec)
     for l in range(lo, lo + n_layers):
         ora.load_tensors(l, synth.layer_tensors(one, SEED, l))
-    x = synth.hidden_states(one, SEED + 1, batch * prompt)
+    x = synth.hidden_states(one, SEED + 1, sum(lengths))
     t0 = time.perf_counter()
-    ora.prefill(x, [prompt] * batch)
+    ora.prefill(x, lengths)
     for t in range(n_dec):
         ora.decode(synth.hidden_states(one, SEED + 2 + t, batch))
     dt = time.perf_counter() - t0
     threads = max([p["num_threads"] for p in threadpoolctl.threadpool_info()] or [1])
-    return dt, batch * (prompt + n_dec), threads, n_layers, n_dec
+    return dt, sum(lengths) + batch * n_dec, threads, n_layers, n_dec
 
 
 def execute_while_load(args, synth, st, blocks, shape, batch, prompt, dsteps):
@@ -194,7 +205,9 @@ def main():
     key, lo, hi, batch, prompt, dsteps = WORKLOADS[args.workload]
     shape = synth.CONFIGS[key]
     t_gen = time.perf_counter()
-    st, blocks = build_stage(synth, Stage, pack_block, shape, lo, hi, batch, prompt, dsteps)
+    lengths = prompt_lengths(synth, batch, prompt)
+    max_len = max(lengths)
+    st, blocks = build_stage(synth, Stage, pack_block, shape, lo, hi, lengths, dsteps)
     t_gen = time.perf_counter() - t_gen
     if args.workload.startswith("ewl_"):
         execute_while_load(args, synth, st, blocks, shape, batch, prompt, dsteps)
@@ -212,7 +225,7 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    T = batch * prompt
+    T = sum(lengths)
     if st.first:
         x_prefill = torch.from_numpy(synth.token_ids(SEED + 1, T, shape.vocab)).cuda()
         x_decode = [torch.from_numpy(synth.token_ids(SEED + 2 + t, batch, shape.vocab)).cuda() for t in range(dsteps)]
@@ -225,8 +238,6 @@ def main():
         x_decode = [dev(synth.hidden_states(shape, SEED + 2 + t, batch)) for t in range(dsteps)]
     out_dec = (torch.empty(batch, dtype=torch.int32, device="cuda") if st.last
                else torch.empty(batch, shape.hidden, dtype=st.tdtype, device="cuda"))
-    lengths = [prompt] * batch
-
     ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
     mid_layer = (lo + hi) // 2
 
@@ -237,7 +248,7 @@ def main():
         if timed:
             ev[1].record(stream)
         for t in range(dsteps):
-            st.decode(x_decode[t], batch, prompt + t, out=out_dec)
+            st.decode(x_decode[t], batch, max_len + t, out=out_dec)
         if timed:
             ev[2].record(stream)
 
@@ -287,9 +298,9 @@ def main():
     L = hi - lo
     wbytes = sum(st_block_bytes(st, l) for l in range(lo, hi))
     kv_tok = 2 * shape.n_kv_heads * shape.head_dim * e
-    dec_bytes = sum(wbytes + batch * (prompt + t + 1) * kv_tok * L for t in range(dsteps))
+    dec_bytes = sum(wbytes + (T + batch * (t + 1)) * kv_tok * L for t in range(dsteps))
     p_mm = (shape.qkv_rows * d + d * shape.n_q_heads * shape.head_dim + 3 * F * d)
-    pre_flops = 2.0 * T * p_mm * L + 2.0 * shape.n_q_heads * shape.head_dim * prompt * (prompt + 1) * batch * L
+    pre_flops = 2.0 * T * p_mm * L + sum(2.0 * shape.n_q_heads * shape.head_dim * n * (n + 1) for n in lengths) * L
 
     res = {
         "metric": "stage prefill+decode tokens/s (1 GPU)",
@@ -304,7 +315,8 @@ def main():
         "vs_baseline": None,
         "dtype": "f32" if shape.dtype == "f32" else "bf16",
         "data": "synthetic",
-        "config": {"workload": args.workload, "layers": [lo, hi], "batch": batch, "prompt": prompt,
+        "config": {"workload": args.workload, "layers": [lo, hi], "batch": batch,
+                   "prompt": prompt if isinstance(prompt, int) else {"ragged": list(prompt), "total_tokens": T},
                    "decode_steps": dsteps, "weights_gen_s": round(t_gen, 1)},
         "prefill": {"ms": t_pre, "tokens_per_s": T / (t_pre * 1e-3), "tflops": pre_flops / (t_pre * 1e-3) / 1e12,
                     "frac_of_bf16_mfma_peak": pre_flops / (t_pre * 1e-3) / 1e12 / MFMA_BF16_PEAK_TF},
@@ -320,11 +332,11 @@ def main():
                              "flops_per_launch": pg_flops, "avg_ms": pg_ms, "launches_timed": len(probe_pre)},
     }
     if not args.no_cpu_baseline:
-        dt, ntok, threads, n_layers, n_dec = cpu_baseline(synth, shape, lo, hi, batch, prompt, dsteps)
+        dt, ntok, threads, n_layers, n_dec = cpu_baseline(synth, shape, lo, hi, lengths, dsteps)
         res["cpu_baseline"] = {
             "value": ntok / (dt * L / n_layers), "unit": "tokens/s", "cores": threads, "kind": "oracle",
             "sample": "%d of %d layers at real dims, %d seqs x (%d prompt + %d decode) tokens in %.1f s%s"
-                      % (n_layers, L, batch, prompt, n_dec, dt,
+                      % (n_layers, L, batch, max_len, n_dec, dt,
                          "" if n_layers == L else "; scaled linearly to %d layers (extrapolated)" % L),
         }
     st.close()

@@ -4,11 +4,26 @@
 
 namespace ls {
 
+bool gemm_decode_fusable(int M, int N, int K) { return gemm_skinny_supported(M, N, K); }
+
+size_t gemm_scratch_bytes(int rows, size_t cols) {
+  const size_t r = rows < 64 ? rows : 64;
+  return 8 * r * cols * sizeof(float);  // up to 8 K splits
+}
+
 void launch_gemm(uint32_t dt, Epilogue epi, const void* A, const void* W, int M, int N, int K, void* out,
-                 float* resid, hipStream_t st) {
-  if (dt == BF16 && gemm_skinny_supported(M, N, K)) {
-    launch_gemm_skinny(epi, A, W, M, N, K, out, resid, 0, st);
-    return;
+                 float* resid, hipStream_t st, const GemmScratch* scratch, const SkinnyFusion* fusion) {
+  if (dt == BF16 && M <= 64) {
+    // 17..64 rows: the wide kernel, if its shape constraints hold and the scratch is large enough
+    if (M > 16 && scratch && scratch->splitk && gemm_wide_supported(M, N, K) &&
+        gemm_wide_workspace_bytes(M, N, K, epi == EPI_SWIGLU) <= scratch->bytes) {
+      launch_gemm_wide(epi, A, W, M, N, K, out, resid, scratch->splitk, st, fusion);
+      return;
+    }
+    if (gemm_skinny_supported(M, N, K)) {
+      launch_gemm_skinny(epi, A, W, M, N, K, out, resid, 0, st, fusion);
+      return;
+    }
   }
   if (dt == BF16 && M > 64 && gemm_mfma_supported(M, N, K)) {
     launch_gemm_mfma(epi, A, W, M, N, K, out, resid, st);

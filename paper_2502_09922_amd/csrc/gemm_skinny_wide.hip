@@ -1,0 +1,259 @@
+// bf16 weight-streaming GEMM for decode batches of 17..64 rows: C[M,N] = X[M,K] W[N,K]^T.
+//
+// Still bound by streaming W out of HBM once, but at 17..64 rows the activation operand
+// is no longer negligible: if every wavefront fetched its own X fragments (as the kernel
+// for <= 16 rows does) X would cross the L1 several times more often than W.  So here
+//   * a 256-thread workgroup owns 64 output columns, 16 per wavefront (with SwiGLU: 16 gate
+//     rows + 16 up rows per wavefront), and all four wavefronts walk the SAME K range;
+//   * the X block of a K step (M rows x 256 bytes) is fetched once per workgroup with fully
+//     coalesced 16-byte loads, optionally multiplied by the RMSNorm gain, and staged in LDS
+//     (double buffered, chunks XOR-swizzled by row) in the layout an MFMA B operand reads;
+//   * W streams exactly as in the narrow kernel: 4 loads of 16 rows x 256 contiguous bytes per
+//     wavefront and K step, a register ring two steps deep, a wave-private LDS transpose;
+//   * K is split across gridDim.y workgroups to put enough of them on the chip; each writes
+//     its fp32 partial tile, and k_wide_finish adds the partials in split order (fixed order:
+//     reproducible), applies the row scale of a folded RMSNorm and the epilogue.
+// v_mfma_f32_16x16x32_bf16: W is the A operand (row = lane%16), X the B operand (column
+// m = lane%16 + 16 t); a lane of the result holds m and n = 4*(lane/16) + r.
+#include "kernels.hpp"
+#include "device_util.hpp"
+
+namespace ls {
+
+namespace {
+
+constexpr int WAVES = 4;
+
+template <int MT, bool GLU, bool NORM>
+__global__ void __launch_bounds__(WAVES * 64)
+k_gemm_wide(const bf16* __restrict__ X, const bf16* __restrict__ W, int M, int N, int K,
+            float* __restrict__ part, const bf16* __restrict__ gamma, int blocks_per_split) {
+  constexpr int NW = GLU ? 2 : 1;
+  constexpr int PF = 2;
+  constexpr int XS_BYTES = MT * 16 * 256;  // one staged X block
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  unsigned char* xs = smem;                                   // [2][MT*16 rows][256 B]
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  unsigned char* scratch = smem + 2 * XS_BYTES + wave * (NW * 4096);
+  const int lr = lane & 15, lg = lane >> 4;
+  const int n0 = blockIdx.x * 64 + wave * 16;
+  const int nblk = K >> 7;
+  const int b0 = blockIdx.y * blocks_per_split;
+  const int nb = min(blocks_per_split, nblk - b0);
+
+  size_t woff[NW][4];
+#pragma unroll
+  for (int s = 0; s < NW; ++s)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int row = 4 * i + lg;
+      woff[s][i] = (size_t)(s * N + n0 + row) * K + (size_t)((lr ^ row) << 3);
+    }
+  int a_off[4];
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk) a_off[kk] = lr * 256 + (((kk * 4 + lg) ^ lr) << 4);
+  // X staging: thread owns chunk (tid%16) of rows tid/16 + 16 i
+  const int xc = tid & 15, xr0 = tid >> 4;
+  size_t xoff[MT];
+  int xs_off[MT];
+#pragma unroll
+  for (int i = 0; i < MT; ++i) {
+    const int row = xr0 + 16 * i;
+    xoff[i] = (size_t)min(row, M - 1) * K + (size_t)(xc << 3);
+    xs_off[i] = row * 256 + ((xc ^ (row & 15)) << 4);
+  }
+
+  u32x4 wr[PF][NW][4];
+  u32x4 xg[MT], gg;
+  f32x4 acc[NW][MT];
+#pragma unroll
+  for (int s = 0; s < NW; ++s)
+#pragma unroll
+    for (int t = 0; t < MT; ++t) acc[s][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+#define LS_LOAD_W(slot, blk)                                                           \
+  {                                                                                    \
+    const size_t kb_ = (size_t)(blk) << 7;                                             \
+    _Pragma("unroll") for (int s_ = 0; s_ < NW; ++s_)                                  \
+      _Pragma("unroll") for (int i_ = 0; i_ < 4; ++i_)                                 \
+        wr[slot][s_][i_] = *reinterpret_cast<const u32x4*>(W + woff[s_][i_] + kb_);    \
+  }
+#define LS_LOAD_X(blk)                                                                 \
+  {                                                                                    \
+    const size_t kb_ = (size_t)(blk) << 7;                                             \
+    _Pragma("unroll") for (int i_ = 0; i_ < MT; ++i_)                                  \
+      xg[i_] = *reinterpret_cast<const u32x4*>(X + xoff[i_] + kb_);                    \
+    if constexpr (NORM) gg = *reinterpret_cast<const u32x4*>(gamma + kb_ + (xc << 3)); \
+  }
+#define LS_STORE_X(buf)                                                                \
+  _Pragma("unroll") for (int i_ = 0; i_ < MT; ++i_) {                                  \
+    bf16x8 v_ = __builtin_bit_cast(bf16x8, xg[i_]);                                    \
+    if constexpr (NORM) {                                                              \
+      const bf16x8 g_ = __builtin_bit_cast(bf16x8, gg);                                \
+      _Pragma("unroll") for (int e_ = 0; e_ < 8; ++e_)                                 \
+        v_[e_] = (bf16)((float)v_[e_] * (float)g_[e_]);                                \
+    }                                                                                  \
+    *reinterpret_cast<bf16x8*>(xs + (buf) * XS_BYTES + xs_off[i_]) = v_;               \
+  }
+  // one K step with ring slot `slot`
+#define LS_STEP(slot, b)                                                                        \
+  {                                                                                             \
+    if ((b) + 1 < nb) LS_LOAD_X(b0 + (b) + 1)                                                   \
+    _Pragma("unroll") for (int s_ = 0; s_ < NW; ++s_)                                           \
+      _Pragma("unroll") for (int i_ = 0; i_ < 4; ++i_)                                          \
+        *reinterpret_cast<u32x4*>(scratch + s_ * 4096 + i_ * 1024 + lane * 16) = wr[slot][s_][i_]; \
+    if ((b) + PF < nb) LS_LOAD_W(slot, b0 + (b) + PF)                                           \
+    const unsigned char* xb_ = xs + ((b) & 1) * XS_BYTES;                                       \
+    _Pragma("unroll") for (int kk = 0; kk < 4; ++kk) {                                          \
+      bf16x8 xf_[MT];                                                                           \
+      _Pragma("unroll") for (int t = 0; t < MT; ++t)                                            \
+        xf_[t] = *reinterpret_cast<const bf16x8*>(xb_ + (lr + 16 * t) * 256 + (((kk * 4 + lg) ^ lr) << 4)); \
+      _Pragma("unroll") for (int s_ = 0; s_ < NW; ++s_) {                                       \
+        const bf16x8 af_ = *reinterpret_cast<const bf16x8*>(scratch + s_ * 4096 + a_off[kk]);   \
+        _Pragma("unroll") for (int t = 0; t < MT; ++t)                                          \
+          acc[s_][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af_, xf_[t], acc[s_][t], 0, 0, 0); \
+      }                                                                                         \
+    }                                                                                           \
+    if ((b) + 1 < nb) LS_STORE_X(((b) + 1) & 1)                                                 \
+    __syncthreads();                                                                            \
+  }
+
+  if (nb > 0) {
+    LS_LOAD_X(b0)
+    LS_LOAD_W(0, b0)
+    if (nb > 1) LS_LOAD_W(1, b0 + 1)
+    LS_STORE_X(0)
+    __syncthreads();
+    for (int b = 0; b < nb; b += 2) {  // nb is the same for every wavefront of the workgroup
+      LS_STEP(0, b)
+      if (b + 1 < nb) LS_STEP(1, b + 1)
+    }
+  }
+#undef LS_LOAD_W
+#undef LS_LOAD_X
+#undef LS_STORE_X
+#undef LS_STEP
+
+  // partial tile of this K split: part[split][stream][m][N]
+#pragma unroll
+  for (int s = 0; s < NW; ++s)
+#pragma unroll
+    for (int t = 0; t < MT; ++t) {
+      const int m = lr + 16 * t;
+      if (m < M)
+        *reinterpret_cast<f32x4*>(part + (((size_t)blockIdx.y * NW + s) * M + m) * N + n0 + lg * 4) = acc[s][t];
+    }
+}
+
+// Adds the K-split partials in split order, then the epilogue.  One 256-thread workgroup per
+// (row, 256 columns).
+template <int EPI, bool NORM>
+__global__ void __launch_bounds__(256)
+k_wide_finish(const float* __restrict__ part, int splits, int M, int N, int K, void* __restrict__ outv,
+              float* __restrict__ resid, SkinnyFusion fu) {
+  constexpr int NW = (EPI == EPI_SWIGLU) ? 2 : 1;
+  __shared__ float wsum[4];
+  const int m = blockIdx.y, n = blockIdx.x * 256 + threadIdx.x;
+  float inv = 1.f;
+  if constexpr (NORM) {
+    float ss = 0.f;
+    for (int i = threadIdx.x; i < fu.n_part; i += 256) ss += fu.ss_in[(size_t)m * fu.n_part + i];
+    ss = wave_sum(ss);
+    if ((threadIdx.x & 63) == 0) wsum[threadIdx.x >> 6] = ss;
+    __syncthreads();
+    inv = 1.0f / sqrtf(((wsum[0] + wsum[1]) + (wsum[2] + wsum[3])) / (float)K + fu.eps);
+  }
+  if (n >= N) return;  // N % 16 == 0: 16-lane groups leave together
+  float v[NW];
+#pragma unroll
+  for (int s = 0; s < NW; ++s) {
+    float sum = 0.f;
+    for (int sp = 0; sp < splits; ++sp) sum += part[(((size_t)sp * NW + s) * M + m) * N + n];
+    v[s] = sum * inv;
+  }
+  const size_t o = (size_t)m * N + n;
+  if constexpr (EPI == EPI_STORE) ((bf16*)outv)[o] = (bf16)v[0];
+  else if constexpr (EPI == EPI_RESID) {
+    const float xn = resid[o] + v[0];
+    resid[o] = xn;
+    if (fu.xb_out) {
+      fu.xb_out[o] = (bf16)xn;
+      float ss = xn * xn;
+#pragma unroll
+      for (int off = 8; off; off >>= 1) ss += __shfl_xor(ss, off);
+      if ((n & 15) == 0) fu.ss_out[(size_t)m * (N >> 4) + (n >> 4)] = ss;
+    }
+  }
+  else if constexpr (EPI == EPI_SWIGLU) ((bf16*)outv)[o] = (bf16)(silu_f(v[0]) * v[NW - 1]);
+  else ((float*)outv)[o] = v[0];
+}
+
+template <int MT, bool GLU, bool NORM>
+void launch_main(const void* X, const void* W, int M, int N, int K, float* part, const bf16* gamma, int splits,
+                 int bps, hipStream_t st) {
+  constexpr int NW = GLU ? 2 : 1;
+  constexpr int smem = 2 * MT * 16 * 256 + WAVES * NW * 4096;
+  static bool attr_set = false;
+  if (!attr_set) {
+    (void)hipFuncSetAttribute((const void*)k_gemm_wide<MT, GLU, NORM>, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    attr_set = true;
+  }
+  dim3 grid(N / 64, splits);
+  k_gemm_wide<MT, GLU, NORM><<<grid, WAVES * 64, smem, st>>>((const bf16*)X, (const bf16*)W, M, N, K, part, gamma, bps);
+}
+
+template <bool GLU, bool NORM>
+void launch_mt(const void* X, const void* W, int M, int N, int K, float* part, const bf16* gamma, int splits, int bps,
+               hipStream_t st) {
+  if (M <= 32) launch_main<2, GLU, NORM>(X, W, M, N, K, part, gamma, splits, bps, st);
+  else launch_main<4, GLU, NORM>(X, W, M, N, K, part, gamma, splits, bps, st);
+}
+
+template <int EPI>
+void launch_finish(const float* part, int splits, int M, int N, int K, void* out, float* resid,
+                   const SkinnyFusion& fu, hipStream_t st) {
+  dim3 grid((N + 255) / 256, M);
+  if (fu.gamma) k_wide_finish<EPI, true><<<grid, 256, 0, st>>>(part, splits, M, N, K, out, resid, fu);
+  else k_wide_finish<EPI, false><<<grid, 256, 0, st>>>(part, splits, M, N, K, out, resid, fu);
+}
+
+}  // namespace
+
+int gemm_wide_splits(int N, int K) {
+  // enough workgroups for 256 CUs (a few each), at least four K steps per split
+  const int tiles = N / 64, nblk = K / 128;
+  int s = 1;
+  while (s < 8 && tiles * s < 512 && nblk / (s * 2) >= 4) s *= 2;
+  return s;
+}
+
+bool gemm_wide_supported(int M, int N, int K) {
+  return M > 16 && M <= 64 && N >= 64 && N % 64 == 0 && K >= 512 && K % 128 == 0;
+}
+
+size_t gemm_wide_workspace_bytes(int M, int N, int K, bool glu) {
+  return (size_t)gemm_wide_splits(N, K) * (glu ? 2 : 1) * M * N * sizeof(float);
+}
+
+void launch_gemm_wide(Epilogue epi, const void* X, const void* W, int M, int N, int K, void* out, float* resid,
+                      float* splitk_ws, hipStream_t st, const SkinnyFusion* fusion) {
+  const SkinnyFusion fu = fusion ? *fusion : SkinnyFusion{};
+  const int splits = gemm_wide_splits(N, K);
+  const int nblk = K / 128, bps = (nblk + splits - 1) / splits;
+  const bool glu = epi == EPI_SWIGLU, norm = fu.gamma != nullptr;
+  if (glu) {
+    if (norm) launch_mt<true, true>(X, W, M, N, K, splitk_ws, fu.gamma, splits, bps, st);
+    else launch_mt<true, false>(X, W, M, N, K, splitk_ws, fu.gamma, splits, bps, st);
+  } else {
+    if (norm) launch_mt<false, true>(X, W, M, N, K, splitk_ws, fu.gamma, splits, bps, st);
+    else launch_mt<false, false>(X, W, M, N, K, splitk_ws, fu.gamma, splits, bps, st);
+  }
+  switch (epi) {
+    case EPI_STORE: launch_finish<EPI_STORE>(splitk_ws, splits, M, N, K, out, resid, fu, st); break;
+    case EPI_RESID: launch_finish<EPI_RESID>(splitk_ws, splits, M, N, K, out, resid, fu, st); break;
+    case EPI_SWIGLU: launch_finish<EPI_SWIGLU>(splitk_ws, splits, M, N, K, out, resid, fu, st); break;
+    case EPI_F32: launch_finish<EPI_F32>(splitk_ws, splits, M, N, K, out, resid, fu, st); break;
+  }
+}
+
+}  // namespace ls

@@ -42,9 +42,22 @@ void launch_store_hidden(uint32_t dt, const float* x, void* out, size_t n, hipSt
 void launch_rmsnorm(uint32_t dt, const float* x, const void* gamma, void* y, int rows, int d,
                     float eps, const int32_t* row_map, hipStream_t st);
 
-// C = A[M,K] * W[N,K]^T with fp32 accumulation; A, W in dtype.
+// Scratch for GEMM kernels that split K across workgroups (fp32 partial tiles).
+struct GemmScratch {
+  float* splitk = nullptr;
+  size_t bytes = 0;
+};
+struct SkinnyFusion;
+
+// C = A[M,K] * W[N,K]^T with fp32 accumulation; A, W in dtype.  `fusion` (decode steps only)
+// folds an RMSNorm into the GEMM; the caller must have checked gemm_decode_fusable().
 void launch_gemm(uint32_t dt, Epilogue epi, const void* A, const void* W, int M, int N, int K,
-                 void* out, float* resid, hipStream_t st);
+                 void* out, float* resid, hipStream_t st, const GemmScratch* scratch = nullptr,
+                 const SkinnyFusion* fusion = nullptr);
+bool gemm_decode_fusable(int M, int N, int K);
+// fp32 bytes of split-K scratch that cover any GEMM of up to `rows` (<= 64) rows and `cols`
+// columns (count 2F for the gate-up projection)
+size_t gemm_scratch_bytes(int rows, size_t cols);
 
 void launch_gemm_generic(uint32_t dt, Epilogue epi, const void* A, const void* W, int M, int N, int K,
                          void* out, float* resid, hipStream_t st);
@@ -72,6 +85,13 @@ struct SkinnyFusion {
 bool gemm_skinny_supported(int M, int N, int K);
 void launch_gemm_skinny(Epilogue epi, const void* X, const void* W, int M, int N, int K, void* out, float* resid,
                         int ks, hipStream_t st, const SkinnyFusion* fusion = nullptr);
+
+// bf16 weight-streaming kernel for decode batches of 17..64 rows (K split across
+// workgroups, X staged once per workgroup); needs N % 64 == 0, K % 128 == 0.
+bool gemm_wide_supported(int M, int N, int K);
+size_t gemm_wide_workspace_bytes(int M, int N, int K, bool glu);
+void launch_gemm_wide(Epilogue epi, const void* X, const void* W, int M, int N, int K, void* out, float* resid,
+                      float* splitk_ws, hipStream_t st, const SkinnyFusion* fusion);
 
 // Rotate q (in place inside qkv) and k by the per-position cos/sin table, write k and v
 // into the cache at [seq][kv head][pos].  qkv is [rows, (Hq+2Hkv)*hd].

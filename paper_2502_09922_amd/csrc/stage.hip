@@ -85,7 +85,7 @@ bool span_ok(const ls_cfg* c, int lo, int hi) {
 
 // ---- workspace carving ------------------------------------------------------------------
 struct Carve {
-  size_t cs, x, y, qkv, attn, h, logits, row_seq, row_pos, last_rows, next_tok, xb, xb2, ss_a, ss_b, total;
+  size_t cs, x, y, qkv, attn, h, logits, row_seq, row_pos, last_rows, next_tok, xb, xb2, ss_a, ss_b, splitk, splitk_bytes, total;
 };
 
 Carve carve(const ls_cfg* c, int lo, int hi) {
@@ -111,6 +111,14 @@ Carve carve(const ls_cfg* c, int lo, int hi) {
   w.xb2 = take(B * d * e);
   w.ss_a = take(B * ((d + 15) / 16) * sizeof(float));
   w.ss_b = take(B * ((d + 15) / 16) * sizeof(float));
+  {
+    // split-K scratch of the decode GEMMs for 17..64 rows (bf16 only)
+    size_t cols = qkv_cols > 2 * (size_t)c->ffn ? qkv_cols : 2 * (size_t)c->ffn;
+    if (d > cols) cols = d;
+    if (last && c->vocab > cols) cols = c->vocab;
+    w.splitk_bytes = (c->dtype == LS_DTYPE_BF16 && B > 16) ? ls::gemm_scratch_bytes((int)B, cols) : 0;
+    w.splitk = take(w.splitk_bytes);
+  }
   (void)lo;
   w.total = off;
   return w;
@@ -378,6 +386,9 @@ ls_status forward(ls_stage* s, bool prefill, const void* in, const int32_t* cu_d
   int32_t* row_seq = (int32_t*)(ws + s->w.row_seq);
   int32_t* row_pos = (int32_t*)(ws + s->w.row_pos);
   int32_t* last_rows = (int32_t*)(ws + s->w.last_rows);
+  GemmScratch gsc;
+  gsc.splitk = s->w.splitk_bytes ? (float*)(ws + s->w.splitk) : nullptr;
+  gsc.bytes = s->w.splitk_bytes;
   const bool timed = s->profiling && prefill;
   const bool probing = s->probe_op != LS_OP_NONE && s->probe_phase == (prefill ? 0 : 1) && !s->probe_a.empty();
 
@@ -397,8 +408,8 @@ ls_status forward(ls_stage* s, bool prefill, const void* in, const int32_t* cu_d
 
   // ---- decode step with the RMSNorms folded into the weight-streaming GEMMs
   const bool fused = !prefill && dt == BF16 && d % 16 == 0 && attn_decode_supported(hq, hkv, hd) &&
-                     gemm_skinny_supported(rows, qkv_cols, d) && gemm_skinny_supported(rows, d, hq * hd) &&
-                     gemm_skinny_supported(rows, F, d) && gemm_skinny_supported(rows, d, F);
+                     gemm_decode_fusable(rows, qkv_cols, d) && gemm_decode_fusable(rows, d, hq * hd) &&
+                     gemm_decode_fusable(rows, F, d) && gemm_decode_fusable(rows, d, F);
   if (fused) {
     __bf16* xb = (__bf16*)(ws + s->w.xb);
     __bf16* xb2 = (__bf16*)(ws + s->w.xb2);
@@ -427,12 +438,12 @@ ls_status forward(ls_stage* s, bool prefill, const void* in, const int32_t* cu_d
       f_gu.gamma = (const __bf16*)(base + sp[3].off); f_gu.ss_in = ss_b; f_gu.n_part = d / 16; f_gu.eps = c.rms_eps;
       // the last layer of a middle stage writes the stage output directly
       f_dn.xb_out = (li == n_layers - 1 && !s->last) ? (__bf16*)out : xb; f_dn.ss_out = ss_a;
-      PROBE(LS_OP_GEMM_QKV, launch_gemm_skinny(EPI_STORE, xb, base + sp[1].off, rows, qkv_cols, d, qkv, nullptr, 0, st, &f_qkv));
+      PROBE(LS_OP_GEMM_QKV, launch_gemm(dt, EPI_STORE, xb, base + sp[1].off, rows, qkv_cols, d, qkv, nullptr, st, &gsc, &f_qkv));
       PROBE(LS_OP_ATTENTION, launch_attention_block(dt, nullptr, batch, 1, qkv, cs, kc, vc, row_seq, row_pos, rows, hq,
                                                     hkv, hd, c.max_seq, attn, st));
-      PROBE(LS_OP_GEMM_O, launch_gemm_skinny(EPI_RESID, attn, base + sp[2].off, rows, d, hq * hd, nullptr, x, 0, st, &f_o));
-      PROBE(LS_OP_GEMM_GATEUP, launch_gemm_skinny(EPI_SWIGLU, xb2, base + sp[4].off, rows, F, d, hbuf, nullptr, 0, st, &f_gu));
-      PROBE(LS_OP_GEMM_DOWN, launch_gemm_skinny(EPI_RESID, hbuf, base + sp[5].off, rows, d, F, nullptr, x, 0, st, &f_dn));
+      PROBE(LS_OP_GEMM_O, launch_gemm(dt, EPI_RESID, attn, base + sp[2].off, rows, d, hq * hd, nullptr, x, st, &gsc, &f_o));
+      PROBE(LS_OP_GEMM_GATEUP, launch_gemm(dt, EPI_SWIGLU, xb2, base + sp[4].off, rows, F, d, hbuf, nullptr, st, &gsc, &f_gu));
+      PROBE(LS_OP_GEMM_DOWN, launch_gemm(dt, EPI_RESID, hbuf, base + sp[5].off, rows, d, F, nullptr, x, st, &gsc, &f_dn));
     }
     if (s->last) {
       const Block* hb = s->find(s->hi);
@@ -442,7 +453,7 @@ ls_status forward(ls_stage* s, bool prefill, const void* in, const int32_t* cu_d
       LS_HIP(hipStreamWaitEvent(st, hb->loaded, 0));
       float* logits = logits_out ? logits_out : (float*)(ws + s->w.logits);
       launch_rmsnorm(dt, x, base + sp[0].off, y, batch, d, c.rms_eps, last_rows, st);
-      launch_gemm(dt, EPI_F32, y, base + sp[1].off, batch, c.vocab, d, logits, nullptr, st);
+      launch_gemm(dt, EPI_F32, y, base + sp[1].off, batch, c.vocab, d, logits, nullptr, st, &gsc);
       launch_argmax(logits, batch, c.vocab, (int32_t*)out, st);
     }
     LS_HIP(hipGetLastError());
@@ -472,13 +483,13 @@ ls_status forward(ls_stage* s, bool prefill, const void* in, const int32_t* cu_d
     char* vc = (char*)kv->v + li * kv_layer;
 
     PROBE(LS_OP_NORM, launch_rmsnorm(dt, x, base + sp[0].off, y, rows, d, c.rms_eps, nullptr, st));
-    PROBE(LS_OP_GEMM_QKV, launch_gemm(dt, EPI_STORE, y, base + sp[1].off, rows, qkv_cols, d, qkv, nullptr, st));
+    PROBE(LS_OP_GEMM_QKV, launch_gemm(dt, EPI_STORE, y, base + sp[1].off, rows, qkv_cols, d, qkv, nullptr, st, &gsc));
     PROBE(LS_OP_ATTENTION, launch_attention_block(dt, cu_dev, batch, max_len, qkv, cs, kc, vc, row_seq, row_pos, rows,
                                                   hq, hkv, hd, c.max_seq, attn, st));
-    PROBE(LS_OP_GEMM_O, launch_gemm(dt, EPI_RESID, attn, base + sp[2].off, rows, d, hq * hd, nullptr, x, st));
+    PROBE(LS_OP_GEMM_O, launch_gemm(dt, EPI_RESID, attn, base + sp[2].off, rows, d, hq * hd, nullptr, x, st, &gsc));
     launch_rmsnorm(dt, x, base + sp[3].off, y, rows, d, c.rms_eps, nullptr, st);
-    PROBE(LS_OP_GEMM_GATEUP, launch_gemm(dt, EPI_SWIGLU, y, base + sp[4].off, rows, F, d, hbuf, nullptr, st));
-    PROBE(LS_OP_GEMM_DOWN, launch_gemm(dt, EPI_RESID, hbuf, base + sp[5].off, rows, d, F, nullptr, x, st));
+    PROBE(LS_OP_GEMM_GATEUP, launch_gemm(dt, EPI_SWIGLU, y, base + sp[4].off, rows, F, d, hbuf, nullptr, st, &gsc));
+    PROBE(LS_OP_GEMM_DOWN, launch_gemm(dt, EPI_RESID, hbuf, base + sp[5].off, rows, d, F, nullptr, x, st, &gsc));
     if (timed) LS_HIP(hipEventRecord(s->comp_end[li], st));
   }
 #undef PROBE
@@ -492,7 +503,7 @@ ls_status forward(ls_stage* s, bool prefill, const void* in, const int32_t* cu_d
     LS_HIP(hipStreamWaitEvent(st, hb->loaded, 0));  // gate: head block has landed
     float* logits = logits_out ? logits_out : (float*)(ws + s->w.logits);
     launch_rmsnorm(dt, x, base + sp[0].off, y, batch, d, c.rms_eps, last_rows, st);
-    launch_gemm(dt, EPI_F32, y, base + sp[1].off, batch, c.vocab, d, logits, nullptr, st);
+    launch_gemm(dt, EPI_F32, y, base + sp[1].off, batch, c.vocab, d, logits, nullptr, st, &gsc);
     launch_argmax(logits, batch, c.vocab, (int32_t*)out, st);
   } else {
     launch_store_hidden(dt, x, out, (size_t)rows * d, st);
