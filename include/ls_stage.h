@@ -137,6 +137,9 @@ ls_status ls_stage_create(const ls_cfg* cfg, int layer_lo, int layer_hi, void* w
 /* Release the handle and its events.  Does not wait for enqueued work: synchronise first. */
 void ls_stage_destroy(ls_stage* stage);
 
+/* Shape, limits and layer span the stage was created with (any output pointer may be NULL). */
+ls_status ls_stage_info(const ls_stage* stage, ls_cfg* cfg, int* layer_lo, int* layer_hi);
+
 /* Packed size of block `layer` of this stage (0 if the stage does not hold it). */
 size_t ls_stage_block_bytes(const ls_stage* stage, int layer);
 
@@ -240,6 +243,60 @@ ls_status ls_stage_probe(ls_stage* stage, int op, int layer, int phase);
 /* After the caller has synchronised: durations in ms of the probed launches since the
  * probe was set, oldest first, at most `cap`; *n receives the count. */
 ls_status ls_stage_probe_times(ls_stage* stage, float* ms, int cap, int* n);
+
+/* ---- execution pipeline over several stages (2D pipelining) ---------------------------
+ *
+ * Section 4.3, "2D execution pipelines" (Fig. 6a): the stages of one model form a pipeline;
+ * each stage works on a different batch of requests, hands its intermediate result to the
+ * next stage and starts on the next batch.  Here the stages are ls_stage handles whose
+ * spans follow each other ([0,a), [a,b), ...), each driven on its own HIP stream; a batch in
+ * flight is a "micro-batch".  Stage s starts micro-batch m once stage s-1 has finished m
+ * (an event wait on the GPU, no host wait) and, by stream order, once it has finished
+ * m-1 itself.  On one GPU the stages share the device, so this reproduces the dataflow and
+ * its ordering, not the cluster's throughput.
+ */
+typedef struct ls_pipeline ls_pipeline; /* opaque */
+
+/* One micro-batch on its way through the pipeline.  All pointers except cu_seqlens_host,
+ * kv and handoff themselves are device memory owned by the caller. */
+typedef struct {
+  const void* in;                 /* input of the first stage: token ids or hidden states  */
+  const int32_t* cu_seqlens_dev;  /* prompt pass only: as in ls_stage_prefill              */
+  const int32_t* cu_seqlens_host; /* prompt pass only: host copy                           */
+  int32_t batch;                  /* sequences in this micro-batch                         */
+  int32_t total_tokens;           /* prompt pass: rows; generation step: ignored           */
+  int32_t max_ctx;                /* generation step only: as in ls_stage_decode           */
+  const ls_kv* kv;                /* host array [n_stages]: this micro-batch's cache in
+                                     every stage (caches are per stage and per batch)      */
+  void* const* handoff;           /* host array [n_stages-1]: device buffers that carry the
+                                     intermediate result from stage s to s+1, each at least
+                                     rows * hidden elements of dtype                       */
+  void* out;                      /* output of the last stage, as in ls_stage_prefill      */
+  float* logits_out;              /* optional, last stage with an LM head only             */
+} ls_microbatch;
+
+/* Build a pipeline from n_stages >= 1 stages of the same model whose layer spans are
+ * consecutive (stage i ends where stage i+1 begins), else LS_ERR_INVALID_ARG.  The
+ * pipeline borrows the stage handles; they must outlive it.  No GPU work. */
+ls_status ls_pipeline_create(ls_stage* const* stages, int n_stages, ls_pipeline** out);
+
+/* Release the pipeline and its events (not the stages).  Synchronise first. */
+void ls_pipeline_destroy(ls_pipeline* pipe);
+
+/*
+ * Enqueue one pass of n_micro micro-batches through every stage: phase 0 = prompt pass,
+ * phase 1 = one generation step.  hip_streams is a host array of n_stages streams, stage s
+ * runs on hip_streams[s]; they should differ for the stages to overlap.  The hand-off
+ * buffer of (stage s, micro-batch m) may be reused by the next call: stage s does not
+ * overwrite it before stage s+1 has consumed the previous content (event wait).  `in`, `out`
+ * and the caches are not guarded across calls: reuse them only in stream order of the first
+ * / last stage's stream.  Argument errors that the host can see are reported before anything
+ * is enqueued; an error that depends on a stage's own state (a block not yet enqueued for
+ * load: LS_ERR_NOT_LOADED) is reported by that stage's call, after earlier stages of the
+ * same micro-batch have been enqueued.  Only enqueues; never waits for the GPU.
+ */
+ls_status ls_pipeline_run(ls_pipeline* pipe, int phase, const ls_microbatch* mbs, int n_micro,
+                          void* const* hip_streams);
 
 /* Message of the last failing call on this thread ("" if none). */
 const char* ls_last_error(void);

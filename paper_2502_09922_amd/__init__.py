@@ -5,7 +5,7 @@ under the same names; `build` compiles the library in-tree for gfx950.  The bind
 imported on first use, so that `python -m paper_2502_09922_amd.build` can run before the
 library exists; a missing library is an ImportError, never a fallback.
 """
-_LAZY = ("binding", "Stage", "LsError", "ls_cfg", "ls_kv", "make_cfg", "pack_block")
+_LAZY = ("binding", "Stage", "Pipeline", "MicroBatch", "LsError", "ls_cfg", "ls_kv", "ls_microbatch", "make_cfg", "pack_block")
 
 
 def __getattr__(name):

@@ -50,6 +50,15 @@ class ls_kv(C.Structure):
     _fields_ = [("k", C.c_void_p), ("v", C.c_void_p), ("seq_lens", C.c_void_p)]
 
 
+class ls_microbatch(C.Structure):
+    _fields_ = [
+        ("in_", C.c_void_p), ("cu_seqlens_dev", C.c_void_p), ("cu_seqlens_host", C.POINTER(C.c_int32)),
+        ("batch", C.c_int32), ("total_tokens", C.c_int32), ("max_ctx", C.c_int32),
+        ("kv", C.POINTER(ls_kv)), ("handoff", C.POINTER(C.c_void_p)), ("out", C.c_void_p),
+        ("logits_out", C.c_void_p),
+    ]
+
+
 _P = C.c_void_p
 _SIGS = {
     "ls_block_bytes": (C.c_size_t, [C.POINTER(ls_cfg), C.c_int]),
@@ -71,6 +80,10 @@ _SIGS = {
     "ls_stage_layer_times": (C.c_int, [_P, C.POINTER(C.c_float), C.POINTER(C.c_float), C.POINTER(C.c_float), C.POINTER(C.c_float), C.c_int]),
     "ls_stage_probe": (C.c_int, [_P, C.c_int, C.c_int, C.c_int]),
     "ls_stage_probe_times": (C.c_int, [_P, C.POINTER(C.c_float), C.c_int, C.POINTER(C.c_int)]),
+    "ls_stage_info": (C.c_int, [_P, C.POINTER(ls_cfg), C.POINTER(C.c_int), C.POINTER(C.c_int)]),
+    "ls_pipeline_create": (C.c_int, [C.POINTER(_P), C.c_int, C.POINTER(_P)]),
+    "ls_pipeline_destroy": (None, [_P]),
+    "ls_pipeline_run": (C.c_int, [_P, C.c_int, C.POINTER(ls_microbatch), C.c_int, C.POINTER(_P)]),
     "ls_last_error": (C.c_char_p, []),
 }
 for _name, (_res, _args) in _SIGS.items():
@@ -238,3 +251,115 @@ class Stage:
             "copy_end_ms": list(arrs[2]) if want_copy else None,
             "compute_end_ms": list(arrs[3]),
         }
+
+
+class MicroBatch:
+    """Device buffers of one micro-batch of a Pipeline: a KV cache per stage, hand-off
+    buffers between the stages, the output; allocated with PyTorch."""
+
+    def __init__(self, pipe: "Pipeline", max_rows: int):
+        torch = pipe.torch
+        st0 = pipe.stages[0]
+        self.caches = []
+        for st in pipe.stages:
+            kb = lib.ls_stage_kv_bytes(C.byref(st.cfg), st.lo, st.hi)
+            k = torch.zeros(kb, dtype=torch.uint8, device=st.device)
+            v = torch.zeros(kb, dtype=torch.uint8, device=st.device)
+            sl = torch.zeros(st.cfg.max_batch, dtype=torch.int32, device=st.device)
+            self.caches.append((k, v, sl))
+        self.kv = (ls_kv * len(pipe.stages))(*[ls_kv(k.data_ptr(), v.data_ptr(), sl.data_ptr()) for k, v, sl in self.caches])
+        self.handoff_t = [torch.empty(max_rows, st0.shape.hidden, dtype=st0.tdtype, device=st0.device)
+                          for _ in pipe.stages[1:]]
+        self.handoff = (C.c_void_p * max(1, len(self.handoff_t)))(*[t.data_ptr() for t in self.handoff_t])
+        self.max_rows = max_rows
+
+
+class Pipeline:
+    """ls_pipeline over Stage objects, one torch stream per stage."""
+
+    def __init__(self, stages):
+        self.torch = torch
+        self.stages = list(stages)
+        hs = (_P * len(self.stages))(*[s.handle for s in self.stages])
+        h = _P()
+        check(lib.ls_pipeline_create(hs, len(self.stages), C.byref(h)))
+        self.handle = h
+        self.streams = [torch.cuda.Stream(device=s.device) for s in self.stages]
+        self._stream_ptrs = (_P * len(self.stages))(*[s.cuda_stream for s in self.streams])
+        self._keep = []
+
+    def close(self):
+        if getattr(self, "handle", None):
+            self.torch.cuda.synchronize()
+            lib.ls_pipeline_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _out(self, rows, batch):
+        last = self.stages[-1]
+        if last.last:
+            return self.torch.empty(batch, dtype=self.torch.int32, device=last.device)
+        return self.torch.empty(rows, last.shape.hidden, dtype=last.tdtype, device=last.device)
+
+    def run(self, phase: int, mbs: Sequence[MicroBatch], inputs, lengths=None, max_ctx=None, want_logits=False):
+        """phase 0: lengths[m] = prompt lengths of micro-batch m; phase 1: max_ctx[m] bounds its
+        cached lengths and its batch is len(inputs[m]).  Returns the outputs (and logits)."""
+        torch = self.torch
+        arr = (ls_microbatch * len(mbs))()
+        outs, logits, keep = [], [], []
+        last = self.stages[-1]
+        for m, mb in enumerate(mbs):
+            if phase == 0:
+                cu = np.zeros(len(lengths[m]) + 1, np.int32)
+                cu[1:] = np.cumsum(np.asarray(lengths[m], dtype=np.int64))
+                batch, rows = len(lengths[m]), int(cu[-1])
+                cu_dev = torch.from_numpy(cu).to(last.device)
+                keep += [cu, cu_dev]
+                arr[m].cu_seqlens_dev = cu_dev.data_ptr()
+                arr[m].cu_seqlens_host = cu.ctypes.data_as(C.POINTER(C.c_int32))
+                arr[m].total_tokens = rows
+            else:
+                batch = rows = int(inputs[m].shape[0])
+                arr[m].max_ctx = int(max_ctx[m])
+            if rows > mb.max_rows:
+                raise ValueError("micro-batch %d has %d rows, its hand-off buffers hold %d" % (m, rows, mb.max_rows))
+            out = self._out(rows, batch)
+            lg = (torch.empty(batch, last.shape.vocab, dtype=torch.float32, device=last.device)
+                  if (want_logits and last.last) else None)
+            arr[m].in_ = inputs[m].data_ptr()
+            arr[m].batch = batch
+            arr[m].kv = mb.kv
+            arr[m].handoff = mb.handoff
+            arr[m].out = out.data_ptr()
+            arr[m].logits_out = lg.data_ptr() if lg is not None else None
+            outs.append(out)
+            logits.append(lg)
+        # inputs were produced on the current stream or, when a step feeds on the previous
+        # one's tokens, on the last stage's stream: the stage streams wait for both
+        cur = torch.cuda.current_stream()
+        for s in self.streams:
+            s.wait_stream(cur)
+        self.streams[0].wait_stream(self.streams[-1])
+        # buffers allocated on the current stream are used on the stage streams
+        for t in outs + [l for l in logits if l is not None]:
+            t.record_stream(self.streams[-1])
+        for t in keep:
+            if hasattr(t, "record_stream"):
+                for s in self.streams:
+                    t.record_stream(s)
+        for t in inputs:
+            t.record_stream(self.streams[0])
+        check(lib.ls_pipeline_run(self.handle, phase, arr, len(mbs), self._stream_ptrs))
+        self._keep = [keep, list(inputs), outs, logits]
+        return (outs, logits) if want_logits else outs
+
+    def join(self):
+        """Order the current torch stream after everything the pipeline has enqueued."""
+        cur = self.torch.cuda.current_stream()
+        for s in self.streams:
+            cur.wait_stream(s)

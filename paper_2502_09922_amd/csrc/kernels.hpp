@@ -9,6 +9,9 @@ namespace ls {
 
 enum : uint32_t { F32 = 0, BF16 = 1 };
 
+// printf-style setter of the thread-local message behind ls_last_error()
+void set_last_error(const char* fmt, ...);
+
 // What a GEMM does with its fp32 accumulators.
 enum Epilogue : int {
   EPI_STORE = 0,   // out[M,N] in dtype

@@ -29,6 +29,18 @@ ls_status fail(ls_status code, const char* fmt, ...) {
     if (e_ != hipSuccess) return fail(LS_ERR_HIP, "%s: %s", #call, hipGetErrorString(e_)); \
   } while (0)
 
+}  // namespace
+
+// Lets the other host-side sources of the library set the message ls_last_error() returns.
+void ls::set_last_error(const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof g_err, fmt, ap);
+  va_end(ap);
+}
+
+namespace {
+
 constexpr size_t ALIGN = 256;
 inline size_t up(size_t n) { return (n + ALIGN - 1) / ALIGN * ALIGN; }
 inline size_t isz(const ls_cfg* c) { return c->dtype == LS_DTYPE_F32 ? 4 : 2; }
@@ -304,6 +316,14 @@ void ls_stage_destroy(ls_stage* s) {
   for (auto e : s->probe_a) (void)hipEventDestroy(e);
   for (auto e : s->probe_b) (void)hipEventDestroy(e);
   delete s;
+}
+
+ls_status ls_stage_info(const ls_stage* s, ls_cfg* cfg, int* lo, int* hi) {
+  if (!s) return fail(LS_ERR_INVALID_ARG, "ls_stage_info: NULL stage");
+  if (cfg) *cfg = s->cfg;
+  if (lo) *lo = s->lo;
+  if (hi) *hi = s->hi;
+  return LS_OK;
 }
 
 size_t ls_stage_block_bytes(const ls_stage* s, int layer) {

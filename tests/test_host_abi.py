@@ -97,3 +97,15 @@ def test_argument_errors_are_reported_before_any_device_work():
     assert b.ls_stage_block_bytes(None, 0) == 0
     off, nb = C.c_size_t(), C.c_size_t()
     assert b.ls_block_tensor(C.byref(cfg), 0, 6, C.byref(off), C.byref(nb)) == b.LS_ERR_INVALID_ARG
+
+
+def test_pipeline_argument_errors_need_no_gpu():
+    h = C.c_void_p()
+    assert b.ls_pipeline_create(None, 1, C.byref(h)) == b.LS_ERR_INVALID_ARG
+    none = (C.c_void_p * 1)(None)
+    assert b.ls_pipeline_create(none, 1, C.byref(h)) == b.LS_ERR_INVALID_ARG
+    assert b.ls_pipeline_create(none, 0, C.byref(h)) == b.LS_ERR_INVALID_ARG
+    assert h.value is None
+    assert b.ls_pipeline_run(None, 0, None, 1, None) == b.LS_ERR_INVALID_ARG
+    assert b.ls_stage_info(None, None, None, None) == b.LS_ERR_INVALID_ARG
+    b.ls_pipeline_destroy(None)  # a no-op
