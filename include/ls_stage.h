@@ -298,6 +298,42 @@ void ls_pipeline_destroy(ls_pipeline* pipe);
 ls_status ls_pipeline_run(ls_pipeline* pipe, int phase, const ls_microbatch* mbs, int n_micro,
                           void* const* hip_streams);
 
+/* ---- planning (pure integer functions, host only, no GPU) --------------------------------
+ *
+ * Section 4.2: a model of n_blocks ordered blocks is multicast from k source nodes to the
+ * rest of N nodes; the nodes form k sub-groups, each fed by one source.  Algorithm 1 cuts
+ * the blocks into k chunks of ceil(n_blocks/k) and lets sub-group g receive the chunks in
+ * circularly shifted order g, g+1, ..., so that after ceil(n_blocks/k) steps the sub-groups
+ * together hold a whole model.  Section 4.3, Algorithm 2 then builds execution pipelines from
+ * one node of every sub-group; the node of sub-group g runs chunk g, i.e. the stage
+ * [lo, hi) of ls_plan_chunk_span.  Indices are 0-based.
+ */
+
+/* Blocks [*lo, *hi) of chunk `chunk` (0 <= chunk < k); trailing chunks may be empty. */
+ls_status ls_plan_chunk_span(int n_blocks, int k, int chunk, int* lo, int* hi);
+
+/* order[0..n_blocks): the order in which sub-group `group` (0 <= group < k) receives the
+ * blocks, e.g. the order to hand them to ls_stage_load_block (Algorithm 1). */
+ls_status ls_plan_kway_order(int n_blocks, int k, int group, int32_t* order);
+
+/* sizes[0..k): nodes per sub-group when n_nodes >= k nodes are dealt out as evenly as
+ * possible (the first n_nodes % k sub-groups hold one node more). */
+ls_status ls_plan_subgroup_sizes(int n_nodes, int k, int32_t* sizes);
+
+/*
+ * Execution pipelines from sub-groups with sizes[i] joinable nodes each (Algorithm 2).
+ * Pipeline p consists of the nodes (group_out[j], index_out[j]), pipe_start[p] <= j <
+ * pipe_start[p+1], in pipeline order; *n_pipes pipelines are written.  group_out and
+ * index_out hold `capacity` entries (LS_ERR_OOM if the sizes sum to more), pipe_start
+ * capacity + 1.
+ */
+ls_status ls_plan_pipelines(const int32_t* sizes, int k, int32_t* group_out, int32_t* index_out,
+                            int32_t* pipe_start, int capacity, int* n_pipes);
+
+/* Steps a 1 -> n_nodes binomial-pipeline multicast of n_blocks blocks takes:
+ * n_blocks + ceil(log2 n_nodes) - 1 (Section 4.2); LS_ERR_INVALID_ARG (negative) on bad input. */
+int ls_plan_multicast_steps(int n_blocks, int n_nodes);
+
 /* Message of the last failing call on this thread ("" if none). */
 const char* ls_last_error(void);
 

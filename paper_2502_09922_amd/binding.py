@@ -84,6 +84,12 @@ _SIGS = {
     "ls_pipeline_create": (C.c_int, [C.POINTER(_P), C.c_int, C.POINTER(_P)]),
     "ls_pipeline_destroy": (None, [_P]),
     "ls_pipeline_run": (C.c_int, [_P, C.c_int, C.POINTER(ls_microbatch), C.c_int, C.POINTER(_P)]),
+    "ls_plan_chunk_span": (C.c_int, [C.c_int, C.c_int, C.c_int, C.POINTER(C.c_int), C.POINTER(C.c_int)]),
+    "ls_plan_kway_order": (C.c_int, [C.c_int, C.c_int, C.c_int, C.POINTER(C.c_int32)]),
+    "ls_plan_subgroup_sizes": (C.c_int, [C.c_int, C.c_int, C.POINTER(C.c_int32)]),
+    "ls_plan_pipelines": (C.c_int, [C.POINTER(C.c_int32), C.c_int, C.POINTER(C.c_int32), C.POINTER(C.c_int32),
+                                    C.POINTER(C.c_int32), C.c_int, C.POINTER(C.c_int)]),
+    "ls_plan_multicast_steps": (C.c_int, [C.c_int, C.c_int]),
     "ls_last_error": (C.c_char_p, []),
 }
 for _name, (_res, _args) in _SIGS.items():

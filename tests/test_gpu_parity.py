@@ -136,7 +136,17 @@ def test_streamed_equals_preloaded_bitwise_any_arrival_order_and_no_early_reads(
     torch.cuda.synchronize()
     ref_tok, ref_lg = pre.prefill(tok, lengths, want_logits=True)
     ref_k = pre.k.clone()
-    for order in ([-1, 0, 1, 2, 3], [1, 2, 3, -1, 0]):
+    import ctypes as C
+    from paper_2502_09922_amd import binding as b
+
+    ids = [-1, 0, 1, 2, 3]
+    orders = []
+    for group in (0, 1):  # the orders Algorithm 1 gives two sub-groups for these 5 blocks
+        arr = (C.c_int32 * len(ids))()
+        assert b.ls_plan_kway_order(len(ids), 2, group, arr) == 0
+        orders.append([ids[i] for i in arr])
+    assert orders == [[-1, 0, 1, 2, 3], [2, 3, -1, 0, 1]]
+    for order in orders:
         st = make_gpu(shape, seed, 0, 3, B, S + 1, sum(lengths), load=False)
         st.slab.view(torch.int16).fill_(0x7FC0)  # bf16 NaN everywhere
         blocks = {l: st.stage_host_block(l, buf) for l, buf in packed_blocks(st, seed).items()}
