@@ -157,6 +157,16 @@ size_t ls_stage_block_bytes(const ls_stage* stage, int layer);
  */
 ls_status ls_stage_load_block(ls_stage* stage, const void* host_ptr, int layer, void* hip_stream);
 
+/*
+ * Coarser blocks: copy the packed blocks of decoder layers layer_first..layer_last (both in
+ * [lo, hi), consecutive in the slab and in host memory at host_ptr, back to back) with ONE
+ * bulk copy and gate all of them on its completion.  Same rules as ls_stage_load_block; if
+ * any of the layers is already enqueued nothing is enqueued.  (Section 7.6 studies the block
+ * count; one block per layer is the default granularity here.)
+ */
+ls_status ls_stage_load_layers(ls_stage* stage, const void* host_ptr, int layer_first, int layer_last,
+                               void* hip_stream);
+
 /* Mark `layer`'s block as loaded without copying: the caller has already placed the
  * packed bytes at ls_stage_block_device_ptr() and ordered that write before hip_stream's
  * current tail (the hot-start case of Section 5, model already in GPU memory). */

@@ -72,6 +72,7 @@ _SIGS = {
     "ls_stage_block_bytes": (C.c_size_t, [_P, C.c_int]),
     "ls_stage_block_device_ptr": (_P, [_P, C.c_int]),
     "ls_stage_load_block": (C.c_int, [_P, _P, C.c_int, _P]),
+    "ls_stage_load_layers": (C.c_int, [_P, _P, C.c_int, C.c_int, _P]),
     "ls_stage_adopt_block": (C.c_int, [_P, C.c_int, _P]),
     "ls_stage_reset_blocks": (C.c_int, [_P]),
     "ls_stage_prefill": (C.c_int, [_P, _P, _P, C.POINTER(C.c_int32), C.c_int, C.c_int, C.POINTER(ls_kv), _P, _P, _P]),
@@ -202,6 +203,10 @@ class Stage:
         """host: pinned torch uint8 tensor or numpy uint8 array holding the packed block."""
         ptr = host.data_ptr() if hasattr(host, "data_ptr") else host.ctypes.data
         check(lib.ls_stage_load_block(self.handle, ptr, layer, self._stream_ptr(stream)))
+
+    def load_layers(self, first: int, last: int, host, stream=None):
+        """host: pinned uint8 tensor holding the packed blocks of layers first..last back to back."""
+        check(lib.ls_stage_load_layers(self.handle, host.data_ptr(), first, last, self._stream_ptr(stream)))
 
     def reset_blocks(self):
         check(lib.ls_stage_reset_blocks(self.handle))

@@ -355,6 +355,32 @@ ls_status ls_stage_load_block(ls_stage* s, const void* host_ptr, int layer, void
   return LS_OK;
 }
 
+ls_status ls_stage_load_layers(ls_stage* s, const void* host_ptr, int first, int last, void* hip_stream) {
+  if (!s || !host_ptr) return fail(LS_ERR_INVALID_ARG, "ls_stage_load_layers: NULL argument");
+  if (first < s->lo || last >= s->hi || first > last)
+    return fail(LS_ERR_BLOCK_RANGE, "ls_stage_load_layers: layers [%d,%d] outside stage [%d,%d)", first, last, s->lo, s->hi);
+  Block* b0 = s->find(first);
+  size_t bytes = 0;
+  for (int l = first; l <= last; ++l) {
+    Block* b = s->find(l);
+    if (b->state != NOT_LOADED) return fail(LS_ERR_ALREADY_LOADED, "ls_stage_load_layers: block %d already enqueued", l);
+    bytes += b->bytes;
+  }
+  hipStream_t st = (hipStream_t)hip_stream;
+  if (s->profiling) {
+    for (int l = first; l <= last; ++l) LS_HIP(hipEventRecord(s->find(l)->copy_start, st));
+    if (s->origin_block < 0) s->origin_block = (int)(b0 - s->blocks.data());
+  }
+  LS_HIP(hipMemcpyAsync(s->slab + b0->off, host_ptr, bytes, hipMemcpyHostToDevice, st));
+  for (int l = first; l <= last; ++l) {
+    Block* b = s->find(l);
+    b->timed = s->profiling;
+    LS_HIP(hipEventRecord(b->loaded, st));
+    b->state = ENQUEUED;
+  }
+  return LS_OK;
+}
+
 ls_status ls_stage_adopt_block(ls_stage* s, int layer, void* hip_stream) {
   if (!s) return fail(LS_ERR_INVALID_ARG, "ls_stage_adopt_block: NULL stage");
   Block* b = s->find(layer);

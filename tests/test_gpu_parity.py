@@ -250,3 +250,36 @@ def test_layer_times_show_the_gate_and_the_overlap():
     with pytest.raises(LsError):
         st.probe(b.LS_OP_GEMM_QKV, 7, 0)
     st.close()
+
+
+def test_coarse_blocks_of_several_layers_equal_per_layer_blocks():
+    """ls_stage_load_layers: one bulk copy for layers 0..1, another for layer 2, gives the
+    same bits as one copy per layer; overlapping or out-of-range requests enqueue nothing."""
+    import torch
+    from paper_2502_09922_amd import LsError, binding as b
+
+    shape, seed, lengths = MINI_BF16, 9, [40, 7, 90]
+    B, S = len(lengths), max(lengths)
+    tok = to_dev(shape, synth.token_ids(seed + 1, sum(lengths), shape.vocab))
+    pre = make_gpu(shape, seed, 0, 3, B, S + 1, sum(lengths))
+    ref_tok, ref_lg = pre.prefill(tok, lengths, want_logits=True)
+    st = make_gpu(shape, seed, 0, 3, B, S + 1, sum(lengths), load=False)
+    st.slab.view(torch.int16).fill_(0x7FC0)
+    packed = packed_blocks(st, seed)
+    two = st.stage_host_block(100, np.concatenate([packed[0], packed[1]]))
+    copy_stream = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    with pytest.raises(LsError) as e:
+        st.load_layers(1, 3, two, stream=copy_stream)
+    assert e.value.status == b.LS_ERR_BLOCK_RANGE
+    st.load_block(2, st.stage_host_block(2, packed[2]), stream=copy_stream)
+    with pytest.raises(LsError) as e:  # layer 2 is already enqueued: nothing of 1..2 is copied
+        st.load_layers(1, 2, two, stream=copy_stream)
+    assert e.value.status == b.LS_ERR_ALREADY_LOADED
+    st.load_layers(0, 1, two, stream=copy_stream)
+    for l in (-1, 3):
+        st.load_block(l, st.stage_host_block(l, packed[l]), stream=copy_stream)
+    got_tok, got_lg = st.prefill(tok, lengths, want_logits=True)
+    torch.cuda.synchronize()
+    assert torch.equal(got_lg, ref_lg) and torch.equal(got_tok, ref_tok)
+    st.close(); pre.close()
