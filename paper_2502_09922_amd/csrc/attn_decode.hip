@@ -100,15 +100,15 @@ k_attn_decode(const bf16* __restrict__ qkv, int qkv_stride, const float2* __rest
     m[g] = mn_;                                                                              \
   }
 
-  // the cache stream is software pipelined: the loads of the next group of U*KPI keys are
+  // the cache is read once per step: non-temporal loads.  The cache stream is software pipelined: the loads of the next group of U*KPI keys are
   // in flight while the current group is folded into the softmax state; a load whose keys
   // all lie past the wave's range is not issued at all
 #define LS_LOAD_GROUP(buf, j0_)                                                               \
   _Pragma("unroll") for (int u = 0; u < U; ++u) {                                             \
     if ((j0_) + u * KPI < k_end) {                                                            \
       const int key_ = min((j0_) + u * KPI + slot, ctx - 1); /* clamped: a valid cache row */ \
-      kf[buf][u] = *reinterpret_cast<const bf16x8*>(kb + (size_t)key_ * HD + dl * 8);         \
-      vf[buf][u] = *reinterpret_cast<const bf16x8*>(vb + (size_t)key_ * HD + dl * 8);         \
+      kf[buf][u] = __builtin_nontemporal_load(reinterpret_cast<const bf16x8*>(kb + (size_t)key_ * HD + dl * 8)); \
+      vf[buf][u] = __builtin_nontemporal_load(reinterpret_cast<const bf16x8*>(vb + (size_t)key_ * HD + dl * 8)); \
     }                                                                                         \
   }
 #define LS_FOLD_GROUP(buf, j0_)                                                               \

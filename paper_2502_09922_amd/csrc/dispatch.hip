@@ -38,6 +38,10 @@ void launch_attention_block(uint32_t dt, const int32_t* cu_seqlens, int batch, i
                             hipStream_t st) {
   const bool decode = cu_seqlens == nullptr;
   const int qkv_stride = (hq + 2 * hkv) * hd;
+  if (dt == BF16 && decode && attn_decode_gqa_supported(hq, hkv, hd)) {
+    launch_attn_decode_gqa(qkv, qkv_stride, cs_table, kcache, vcache, row_seq, row_pos, rows, hq, hkv, max_seq, out, st);
+    return;
+  }
   if (dt == BF16 && decode && attn_decode_supported(hq, hkv, hd)) {
     launch_attn_decode(qkv, qkv_stride, cs_table, kcache, vcache, row_seq, row_pos, rows, hq, hkv, hd, max_seq, out, st);
     return;

@@ -76,7 +76,7 @@ k_gemm_wide(const bf16* __restrict__ X, const bf16* __restrict__ W, int M, int N
     const size_t kb_ = (size_t)(blk) << 7;                                             \
     _Pragma("unroll") for (int s_ = 0; s_ < NW; ++s_)                                  \
       _Pragma("unroll") for (int i_ = 0; i_ < 4; ++i_)                                 \
-        wr[slot][s_][i_] = *reinterpret_cast<const u32x4*>(W + woff[s_][i_] + kb_);    \
+        wr[slot][s_][i_] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(W + woff[s_][i_] + kb_)); \
   }
 #define LS_LOAD_X(blk)                                                                 \
   {                                                                                    \

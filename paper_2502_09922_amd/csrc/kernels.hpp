@@ -121,6 +121,13 @@ void launch_attn_decode(const void* qkv, int qkv_stride, const float* cs_table, 
                         const int32_t* row_seq, const int32_t* row_pos, int rows, int hq, int hkv, int hd,
                         int max_seq, void* out, hipStream_t st);
 
+// bf16 decode attention on the matrix cores for grouped-query models (head_dim 128,
+// 2 <= Hq/Hkv <= 16), fused with RoPE and the cache append like launch_attn_decode.
+bool attn_decode_gqa_supported(int hq, int hkv, int hd);
+void launch_attn_decode_gqa(const void* qkv, int qkv_stride, const float* cs_table, void* kc, void* vc,
+                            const int32_t* row_seq, const int32_t* row_pos, int rows, int hq, int hkv, int max_seq,
+                            void* out, hipStream_t st);
+
 // bf16 flash-style causal attention for the prompt pass; head_dim 64 or 128.
 bool attn_prefill_supported(int hq, int hkv, int hd);
 void launch_attn_prefill(const void* qkv, int qkv_stride, const void* kc, const void* vc, const int32_t* cu_seqlens,

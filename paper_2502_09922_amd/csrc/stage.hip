@@ -453,7 +453,8 @@ ls_status forward(ls_stage* s, bool prefill, const void* in, const int32_t* cu_d
   const size_t kv_layer = (size_t)c.max_batch * hkv * c.max_seq * hd * e;
 
   // ---- decode step with the RMSNorms folded into the weight-streaming GEMMs
-  const bool fused = !prefill && dt == BF16 && d % 16 == 0 && attn_decode_supported(hq, hkv, hd) &&
+  const bool fused = !prefill && dt == BF16 && d % 16 == 0 &&
+                     (attn_decode_supported(hq, hkv, hd) || attn_decode_gqa_supported(hq, hkv, hd)) &&
                      gemm_decode_fusable(rows, qkv_cols, d) && gemm_decode_fusable(rows, d, hq * hd) &&
                      gemm_decode_fusable(rows, F, d) && gemm_decode_fusable(rows, d, F);
   if (fused) {

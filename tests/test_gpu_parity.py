@@ -75,6 +75,10 @@ def test_mini_bf16_ragged_whole_model():
 @pytest.mark.parametrize("shape,lengths", [
     (MINI_BF16.with_(vocab=0), [70, 3, 129]),
     (MINI_BF16_HD128, [131, 64, 9]),
+    # grouped-query heads of 128: the matrix-core decode attention (3 and 8 heads per kv head),
+    # contexts from under one 32-key tile to several tiles per wavefront
+    (MINI_BF16_HD128.with_(n_kv_heads=2), [131, 64, 9, 1, 31, 32, 33]),
+    (MINI_BF16_HD128.with_(hidden=1024, n_q_heads=8, n_kv_heads=1), [300, 2, 257]),
     (synth.CONFIGS["tiny_f32"].with_(vocab=0), [5, 40, 13]),
 ])
 def test_middle_stage_hidden_parity_and_decode(shape, lengths):
