@@ -94,6 +94,15 @@ k_gemm_skinny(const bf16* __restrict__ X, const bf16* __restrict__ W, int M, int
   for (int p = 0; p < PF; ++p)
     if (p < nb) LS_LOAD_BLOCK(p, b0 + p)
 
+  // residual epilogue: the element this thread will update is known now; fetch it while the
+  // weights stream so that its latency is not added after the K-split reduction
+  float resid_pre = 0.f;
+  if constexpr (EPI == EPI_RESID) {
+    const int e0 = threadIdx.x;
+    if (e0 < MT * 256 && (e0 >> 8) * 16 + ((e0 >> 4) & 15) < M)
+      resid_pre = resid[(size_t)((e0 >> 8) * 16 + ((e0 >> 4) & 15)) * N + n0 + (e0 & 15)];
+  }
+
   // (after the weight ring has been requested, so the stream starts first)
   if constexpr (NORM) {
     for (int i = lane; i < nb * 16; i += 64)
@@ -177,7 +186,7 @@ k_gemm_skinny(const bf16* __restrict__ X, const bf16* __restrict__ W, int M, int
     const size_t o = (size_t)m * N + n0 + n;
     if constexpr (EPI == EPI_STORE) ((bf16*)outv)[o] = (bf16)v[0];
     else if constexpr (EPI == EPI_RESID) {
-      const float xn = resid[o] + v[0];
+      const float xn = (e == (int)threadIdx.x ? resid_pre : resid[o]) + v[0];
       resid[o] = xn;
       if (fu.xb_out) {
         fu.xb_out[o] = (bf16)xn;
