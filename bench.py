@@ -76,26 +76,36 @@ def st_block_bytes(st, layer):
 
 def cpu_baseline(synth, shape, lo, hi, lengths, dsteps):
     """The oracle as it stands, timed on this machine's host cores on a bounded sample of the
-    same workload: up to 8 layers of the stage at the real dimensions, the full batch and
-    prompt length, and 8 decode steps; scaled linearly in layers if the stage has more."""
+    same workload: real layer dimensions and prompt lengths, but only as many layers (up to
+    8) and sequences as keep the work near 15 TFLOP of fp64 (about 15-30 s here), and 8
+    decode steps.  Throughput is per layer of the stage, scaled linearly to its layer count."""
     from oracle.stage_oracle import OracleStage
 
     import threadpoolctl
 
-    n_layers, n_dec = min(hi - lo, 8), min(8, dsteps)
-    batch, prompt = len(lengths), max(lengths)
+    p_mm = shape.qkv_rows * shape.hidden + shape.hidden * shape.n_q_heads * shape.head_dim + 3 * shape.ffn * shape.hidden
+    budget = 15e12
+    n_layers = min(hi - lo, 8)
+    while n_layers > 1 and 2.0 * p_mm * n_layers * lengths[0] > budget:
+        n_layers -= 1
+    n_seq, tok = 0, 0
+    while n_seq < len(lengths) and (n_seq == 0 or 2.0 * p_mm * n_layers * (tok + lengths[n_seq]) <= budget):
+        tok += lengths[n_seq]
+        n_seq += 1
+    sample = list(lengths[:n_seq])
+    n_dec = min(8, dsteps)
     one = shape.with_(vocab=0)
-    ora = OracleStage(one, lo, lo + n_layers, batch, prompt + n_dec)
+    ora = OracleStage(one, lo, lo + n_layers, n_seq, max(sample) + n_dec)
     for l in range(lo, lo + n_layers):
         ora.load_tensors(l, synth.layer_tensors(one, SEED, l))
-    x = synth.hidden_states(one, SEED + 1, sum(lengths))
+    x = synth.hidden_states(one, SEED + 1, sum(sample))
     t0 = time.perf_counter()
-    ora.prefill(x, lengths)
+    ora.prefill(x, sample)
     for t in range(n_dec):
-        ora.decode(synth.hidden_states(one, SEED + 2 + t, batch))
+        ora.decode(synth.hidden_states(one, SEED + 2 + t, n_seq))
     dt = time.perf_counter() - t0
     threads = max([p["num_threads"] for p in threadpoolctl.threadpool_info()] or [1])
-    return dt, sum(lengths) + batch * n_dec, threads, n_layers, n_dec
+    return dt, sum(sample) + n_seq * n_dec, threads, n_layers, n_dec, n_seq, max(sample)
 
 
 def execute_while_load(args, synth, st, blocks, shape, batch, prompt, dsteps):
@@ -332,11 +342,12 @@ def main():
                              "flops_per_launch": pg_flops, "avg_ms": pg_ms, "launches_timed": len(probe_pre)},
     }
     if not args.no_cpu_baseline:
-        dt, ntok, threads, n_layers, n_dec = cpu_baseline(synth, shape, lo, hi, lengths, dsteps)
+        dt, ntok, threads, n_layers, n_dec, n_seq, s_max = cpu_baseline(synth, shape, lo, hi, lengths, dsteps)
         res["cpu_baseline"] = {
             "value": ntok / (dt * L / n_layers), "unit": "tokens/s", "cores": threads, "kind": "oracle",
-            "sample": "%d of %d layers at real dims, %d seqs x (%d prompt + %d decode) tokens in %.1f s%s"
-                      % (n_layers, L, batch, max_len, n_dec, dt,
+            "sample": "%d of %d layers at real dims, %d of %d seqs (prompts up to %d, %d decode steps each), "
+                      "%d tokens in %.1f s%s"
+                      % (n_layers, L, n_seq, batch, s_max, n_dec, ntok, dt,
                          "" if n_layers == L else "; scaled linearly to %d layers (extrapolated)" % L),
         }
     st.close()
