@@ -111,3 +111,47 @@ def test_decode_with_many_sequences(batch):
         row_err = np.linalg.norm(got - want, axis=1) / np.linalg.norm(want, axis=1)
         assert row_err.max() <= 3 * TOL
     gpu.close()
+
+
+@pytest.mark.parametrize("name,layer,batch,prompt,picks", [
+    # bench slices of the larger configurations, one layer of each at the full batch: the
+    # launch shapes bench.py times (many-row prompt GEMMs, decode with 32 / 64 rows, ragged
+    # contexts up to 2048 keys for the grouped-query decode attention)
+    ("llama13b", 16, 32, 1024, (0, 21)),
+    ("llama70b", 40, 64, (128, 2048), (3, "longest")),
+])
+def test_bench_slices_of_the_larger_configurations_sampled_sequences(name, layer, batch, prompt, picks):
+    """The GPU runs the whole batch; the oracle recomputes the picked sequences alone
+    (a sequence's rows do not depend on the other sequences of the batch) for the prompt
+    pass and two decode steps."""
+    import bench
+
+    shape, seed, steps = synth.CONFIGS[name].with_(vocab=0), 1234, 2
+    lengths = bench.prompt_lengths(synth, batch, prompt)
+    B, S, T = len(lengths), max(lengths), sum(lengths)
+    tensors = synth.layer_tensors(shape, seed, layer)
+    from paper_2502_09922_amd import Stage, pack_block
+
+    gpu = Stage(shape, layer, layer + 1, B, S + steps, T)
+    gpu.load_block(layer, gpu.stage_host_block(layer, pack_block(gpu.cfg, layer, [tensors[n] for n in synth.TENSOR_ORDER_LAYER])))
+    x = synth.hidden_states(shape, seed + 1, T)
+    got = to_host(gpu.prefill(to_dev(shape, x), lengths))
+    assert np.isfinite(got).all()
+    dec_in = [synth.hidden_states(shape, seed + 2 + t, B) for t in range(steps)]
+    got_dec = [to_host(gpu.decode(to_dev(shape, dec_in[t]), B, S + t)) for t in range(steps)]
+    assert gpu.seq_lens.cpu().numpy()[:B].tolist() == [n + steps for n in lengths]
+    gpu.close()
+    off = np.concatenate([[0], np.cumsum(lengths)])
+    for pick in picks:
+        b = int(np.argmax(lengths)) if pick == "longest" else pick
+        ora = OracleStage(shape, layer, layer + 1, 1, lengths[b] + steps)
+        ora.load_tensors(layer, tensors)
+        want = ora.prefill(x[off[b]:off[b + 1]], [lengths[b]])
+        mine = got[off[b]:off[b + 1]]
+        assert rel_l2(mine, want) <= TOL, (b, rel_l2(mine, want))
+        row_err = np.linalg.norm(mine - want, axis=1) / np.linalg.norm(want, axis=1)
+        assert row_err.max() <= 2 * TOL, (b, row_err.argmax(), row_err.max())
+        for t in range(steps):
+            want_t = ora.decode(dec_in[t][b:b + 1])
+            assert rel_l2(got_dec[t][b:b + 1], want_t) <= TOL, (b, t)
+            assert np.isfinite(got_dec[t]).all()
