@@ -250,6 +250,9 @@ def main():
                else torch.empty(batch, shape.hidden, dtype=st.tdtype, device="cuda"))
     ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
     mid_layer = (lo + hi) // 2
+    PROBED = min(16, dsteps)  # decode steps per step whose gate-up launch is probed
+    probe_lo = (dsteps - PROBED) // 2
+    probe_hi = probe_lo + PROBED
 
     def one_step(timed):
         if timed:
@@ -258,6 +261,12 @@ def main():
         if timed:
             ev[1].record(stream)
         for t in range(dsteps):
+            # the probe (runtime-stamped start/stop events on one layer's gate-up launch) costs
+            # a few microseconds per probed launch: it is on for PROBED decode steps of a step
+            if timed and t == probe_lo:
+                st.probe(B.LS_OP_GEMM_GATEUP, mid_layer, 1)
+            if timed and t == probe_hi:
+                st.probe(B.LS_OP_NONE)
             st.decode(x_decode[t], batch, max_len + t, out=out_dec)
         if timed:
             ev[2].record(stream)
@@ -266,19 +275,21 @@ def main():
         one_step(False)
     torch.cuda.synchronize()
 
-    # probe the decode gate-up GEMM (the kernel that moves the most bytes) of one layer
-    st.probe(B.LS_OP_GEMM_GATEUP, mid_layer, 1)
+    # the decode gate-up GEMM (the kernel that moves the most bytes) of one layer is probed
+    # inside the timed region, see one_step
     t_pre = t_dec = 0.0
     torch.cuda.synchronize()
     t0 = time.perf_counter()
+    probe_dec, dec_exact = [], True
     for _ in range(args.steps):
         one_step(True)
         torch.cuda.synchronize()
         t_pre += ev[0].elapsed_time(ev[1])
         t_dec += ev[1].elapsed_time(ev[2])
+        probe_dec.extend(st.probe_times())
+        dec_exact = dec_exact and st.probe_is_kernel_exact()
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
-    probe_dec = st.probe_times()
     st.probe(B.LS_OP_NONE)
 
     # one more (untimed) prompt pass with the probe on the prefill gate-up GEMM
@@ -287,7 +298,10 @@ def main():
     st.prefill(x_prefill, lengths)
     torch.cuda.synchronize()
     probe_pre = st.probe_times()
+    pre_exact = st.probe_is_kernel_exact()
     st.probe(B.LS_OP_NONE)
+    timing = {True: "the kernel's own start/stop HIP events (stamped by the runtime at launch)",
+              False: "HIP events recorded around the operator's launches (includes launch gaps)"}
 
     ms_step = wall * 1e3 / args.steps
     t_pre /= args.steps
@@ -336,10 +350,12 @@ def main():
         "roofline": {"kernel": "decode gate-up GEMM + SwiGLU", "bound": "hbm", "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": recorded_traffic(args.workload),
-                     "bytes_per_launch": gu_bytes, "avg_ms": gu_ms, "launches_timed": len(probe_dec)},
+                     "bytes_per_launch": gu_bytes, "avg_ms": gu_ms, "launches_timed": len(probe_dec),
+                     "timing": timing[dec_exact]},
         "roofline_prefill": {"kernel": "prefill gate-up GEMM + SwiGLU", "bound": "mfma", "achieved": pg_tf,
                              "peak": MFMA_BF16_PEAK_TF, "unit": "TFLOP/s", "frac": pg_tf / MFMA_BF16_PEAK_TF,
-                             "flops_per_launch": pg_flops, "avg_ms": pg_ms, "launches_timed": len(probe_pre)},
+                             "flops_per_launch": pg_flops, "avg_ms": pg_ms, "launches_timed": len(probe_pre),
+                             "timing": timing[pre_exact]},
     }
     if not args.no_cpu_baseline:
         dt, ntok, threads, n_layers, n_dec, n_seq, s_max = cpu_baseline(synth, shape, lo, hi, lengths, dsteps)

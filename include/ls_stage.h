@@ -245,13 +245,18 @@ ls_status ls_stage_layer_times(ls_stage* stage, float* copy_ms, float* compute_m
 /*
  * Bracket every launch of operator `op` in decoder layer `layer` with a HIP event pair on
  * the call's own stream, in prefill calls (phase 0) or decode calls (phase 1); op
- * LS_OP_NONE switches the probe off.  The last 512 launches are kept.  Used to measure one
+ * LS_OP_NONE switches the probe off and keeps what was recorded; setting an operator starts a new
+ * record.  The last 512 launches are kept.  Used to measure one
  * kernel's duration inside a timed run without a profiler attached.
  */
 ls_status ls_stage_probe(ls_stage* stage, int op, int layer, int phase);
 
 /* After the caller has synchronised: durations in ms of the probed launches since the
- * probe was set, oldest first, at most `cap`; *n receives the count. */
+ * probe was set, oldest first, at most `cap`; *n receives the count.  Where the operator is
+ * one kernel that the library launches with the runtime's per-kernel start/stop events (the
+ * bf16 GEMMs of up to 16 rows and of more than 64 rows), a duration is that kernel's own
+ * start-to-stop time, as a profiler's kernel trace reports it; otherwise it is the span
+ * between two events recorded around the operator's launches, which includes launch gaps. */
 ls_status ls_stage_probe_times(ls_stage* stage, float* ms, int cap, int* n);
 
 /* ---- execution pipeline over several stages (2D pipelining) ---------------------------
@@ -343,6 +348,10 @@ ls_status ls_plan_pipelines(const int32_t* sizes, int k, int32_t* group_out, int
 /* Steps a 1 -> n_nodes binomial-pipeline multicast of n_blocks blocks takes:
  * n_blocks + ceil(log2 n_nodes) - 1 (Section 4.2); LS_ERR_INVALID_ARG (negative) on bad input. */
 int ls_plan_multicast_steps(int n_blocks, int n_nodes);
+
+/* 1 if every duration ls_stage_probe_times would return now is a kernel's own start-to-stop
+ * time, 0 if some are spans between recorded events (or nothing was probed). */
+int ls_stage_probe_is_kernel_exact(const ls_stage* stage);
 
 /* Message of the last failing call on this thread ("" if none). */
 const char* ls_last_error(void);

@@ -81,6 +81,7 @@ _SIGS = {
     "ls_stage_layer_times": (C.c_int, [_P, C.POINTER(C.c_float), C.POINTER(C.c_float), C.POINTER(C.c_float), C.POINTER(C.c_float), C.c_int]),
     "ls_stage_probe": (C.c_int, [_P, C.c_int, C.c_int, C.c_int]),
     "ls_stage_probe_times": (C.c_int, [_P, C.POINTER(C.c_float), C.c_int, C.POINTER(C.c_int)]),
+    "ls_stage_probe_is_kernel_exact": (C.c_int, [_P]),
     "ls_stage_info": (C.c_int, [_P, C.POINTER(ls_cfg), C.POINTER(C.c_int), C.POINTER(C.c_int)]),
     "ls_pipeline_create": (C.c_int, [C.POINTER(_P), C.c_int, C.POINTER(_P)]),
     "ls_pipeline_destroy": (None, [_P]),
@@ -247,6 +248,9 @@ class Stage:
         arr, n = (C.c_float * 512)(), C.c_int()
         check(lib.ls_stage_probe_times(self.handle, arr, 512, C.byref(n)))
         return list(arr[: n.value])
+
+    def probe_is_kernel_exact(self) -> bool:
+        return bool(lib.ls_stage_probe_is_kernel_exact(self.handle))
 
     def set_profiling(self, on: bool):
         check(lib.ls_stage_set_profiling(self.handle, int(on)))

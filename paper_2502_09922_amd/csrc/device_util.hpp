@@ -1,8 +1,25 @@
 // Small device helpers shared by the HIP kernels (gfx950, 64-lane wavefronts).
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
+
+#include "kernels.hpp"
 
 namespace ls {
+
+// kernel<<<grid, block, smem, st>>>(args...), or the same launch with the runtime's per-kernel
+// start/stop events when the stage runtime has armed launch_timing().
+template <typename... KArgs, typename... Args>
+inline void launch_kernel(void (*kernel)(KArgs...), dim3 grid, dim3 block, unsigned smem, hipStream_t st, Args... args) {
+  LaunchTiming& t = launch_timing();
+  if (t.start) {
+    hipExtLaunchKernelGGL(kernel, grid, block, smem, st, t.start, t.stop, 0, static_cast<KArgs>(args)...);
+    t.start = t.stop = nullptr;
+    t.used = true;
+  } else {
+    hipLaunchKernelGGL(kernel, grid, block, smem, st, static_cast<KArgs>(args)...);
+  }
+}
 
 typedef __bf16 bf16;
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));

@@ -191,7 +191,8 @@ void launch_t(const void* A, const void* W, int M, int N, int K, void* out, floa
   const int tiles_n = (N + ncols - 1) / ncols;
   const int nt = tiles_m * tiles_n;
   const int grid = ((nt + 7) / 8) * 8;
-  k_gemm_mfma<EPI><<<grid, 512, SMEM_BYTES, st>>>((const bf16*)A, (const bf16*)W, M, N, K, out, resid, tiles_m, tiles_n);
+  launch_kernel(k_gemm_mfma<EPI>, dim3(grid), dim3(512), SMEM_BYTES, st, (const bf16*)A, (const bf16*)W, M, N, K, out,
+                resid, tiles_m, tiles_n);
 }
 
 }  // namespace

@@ -219,7 +219,8 @@ void launch_kn(const void* X, const void* W, int M, int N, int K, void* out, flo
     (void)hipFuncSetAttribute((const void*)k_gemm_skinny<MT, EPI, KS, PF, NORM>, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
     attr_bytes = smem;
   }
-  k_gemm_skinny<MT, EPI, KS, PF, NORM><<<N / 16, KS * 64, smem, st>>>((const bf16*)X, (const bf16*)W, M, N, K, out, resid, fu);
+  launch_kernel(k_gemm_skinny<MT, EPI, KS, PF, NORM>, dim3(N / 16), dim3(KS * 64), smem, st, (const bf16*)X,
+                (const bf16*)W, M, N, K, out, resid, fu);
 }
 
 template <int MT, int EPI, int KS>

@@ -12,6 +12,15 @@ enum : uint32_t { F32 = 0, BF16 = 1 };
 // printf-style setter of the thread-local message behind ls_last_error()
 void set_last_error(const char* fmt, ...);
 
+// One-shot request to time the next kernel launch that goes through launch_kernel() on this
+// thread: the HIP runtime stamps `start` / `stop` with that kernel's own begin and end (no
+// launch gap inside the span, unlike a pair of events recorded around the launch).
+struct LaunchTiming {
+  hipEvent_t start = nullptr, stop = nullptr;
+  bool used = false;
+};
+LaunchTiming& launch_timing();
+
 // What a GEMM does with its fp32 accumulators.
 enum Epilogue : int {
   EPI_STORE = 0,   // out[M,N] in dtype

@@ -31,6 +31,11 @@ ls_status fail(ls_status code, const char* fmt, ...) {
 
 }  // namespace
 
+ls::LaunchTiming& ls::launch_timing() {
+  thread_local LaunchTiming t;
+  return t;
+}
+
 // Lets the other host-side sources of the library set the message ls_last_error() returns.
 void ls::set_last_error(const char* fmt, ...) {
   va_list ap;
@@ -165,7 +170,9 @@ struct ls_stage {
   // kernel probe: event pairs around one operator of one layer, a ring of PROBE_CAP pairs
   int probe_op, probe_layer, probe_phase;
   size_t probe_count;
-  std::vector<hipEvent_t> probe_a, probe_b;
+  std::vector<hipEvent_t> probe_a, probe_b;    // recorded around the launch(es)
+  std::vector<hipEvent_t> probe_ka, probe_kb;  // stamped by the runtime with the kernel's own start / stop
+  std::vector<char> probe_exact;               // slot holds a kernel-exact pair
 
   Block* find(int layer) {
     for (auto& b : blocks)
@@ -268,6 +275,8 @@ ls_status ls_stage_create(const ls_cfg* cfg, int lo, int hi, void* weight_slab, 
     for (auto e : s->comp_end) (void)hipEventDestroy(e);
     for (auto e : s->probe_a) (void)hipEventDestroy(e);
     for (auto e : s->probe_b) (void)hipEventDestroy(e);
+    for (auto e : s->probe_ka) (void)hipEventDestroy(e);
+    for (auto e : s->probe_kb) (void)hipEventDestroy(e);
     delete s;
   };
   for (auto& b : s->blocks) {
@@ -315,6 +324,8 @@ void ls_stage_destroy(ls_stage* s) {
   for (auto e : s->comp_end) (void)hipEventDestroy(e);
   for (auto e : s->probe_a) (void)hipEventDestroy(e);
   for (auto e : s->probe_b) (void)hipEventDestroy(e);
+  for (auto e : s->probe_ka) (void)hipEventDestroy(e);
+  for (auto e : s->probe_kb) (void)hipEventDestroy(e);
   delete s;
 }
 
@@ -443,9 +454,18 @@ ls_status forward(ls_stage* s, bool prefill, const void* in, const int32_t* cu_d
   do {                                                                           \
     const bool on_ = probing && s->probe_op == (op) && s->probe_layer == b.layer; \
     const size_t slot_ = s->probe_count % PROBE_CAP;                             \
-    if (on_) LS_HIP(hipEventRecord(s->probe_a[slot_], st));                      \
+    if (on_) {                                                                   \
+      LS_HIP(hipEventRecord(s->probe_a[slot_], st));                             \
+      LaunchTiming& lt_ = launch_timing();                                       \
+      lt_.start = s->probe_ka[slot_];                                            \
+      lt_.stop = s->probe_kb[slot_];                                             \
+      lt_.used = false;                                                          \
+    }                                                                            \
     launch;                                                                      \
     if (on_) {                                                                   \
+      LaunchTiming& lt_ = launch_timing();                                       \
+      s->probe_exact[slot_] = lt_.used;                                          \
+      lt_.start = lt_.stop = nullptr;                                            \
       LS_HIP(hipEventRecord(s->probe_b[slot_], st));                             \
       s->probe_count++;                                                          \
     }                                                                            \
@@ -645,19 +665,40 @@ ls_status ls_stage_probe(ls_stage* s, int op, int layer, int phase) {
       s->probe_a.push_back(a);
       s->probe_b.push_back(b);
     }
+    for (int i = 0; i < PROBE_CAP; ++i) {
+      hipEvent_t a = nullptr, b = nullptr;
+      if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) {
+        if (a) (void)hipEventDestroy(a);
+        return fail(LS_ERR_HIP, "ls_stage_probe: hipEventCreate failed");
+      }
+      s->probe_ka.push_back(a);
+      s->probe_kb.push_back(b);
+    }
+    s->probe_exact.assign(PROBE_CAP, 0);
   }
   s->probe_op = op;
   s->probe_layer = layer;
   s->probe_phase = phase;
-  s->probe_count = 0;
+  if (op != LS_OP_NONE) s->probe_count = 0;  // switching off keeps what was recorded readable
   return LS_OK;
+}
+
+int ls_stage_probe_is_kernel_exact(const ls_stage* s) {
+  if (!s || s->probe_exact.empty() || s->probe_count == 0) return 0;
+  const size_t have = s->probe_count < (size_t)PROBE_CAP ? s->probe_count : (size_t)PROBE_CAP;
+  for (size_t i = 0; i < have; ++i)
+    if (!s->probe_exact[i]) return 0;
+  return 1;
 }
 
 ls_status ls_stage_probe_times(ls_stage* s, float* ms, int cap, int* n) {
   if (!s || !ms || !n || cap < 0) return fail(LS_ERR_INVALID_ARG, "ls_stage_probe_times: bad arguments");
   size_t have = s->probe_count < (size_t)PROBE_CAP ? s->probe_count : (size_t)PROBE_CAP;
   if (have > (size_t)cap) have = (size_t)cap;
-  for (size_t i = 0; i < have; ++i) LS_HIP(hipEventElapsedTime(&ms[i], s->probe_a[i], s->probe_b[i]));
+  for (size_t i = 0; i < have; ++i) {
+    if (s->probe_exact[i]) LS_HIP(hipEventElapsedTime(&ms[i], s->probe_ka[i], s->probe_kb[i]));
+    else LS_HIP(hipEventElapsedTime(&ms[i], s->probe_a[i], s->probe_b[i]));
+  }
   *n = (int)have;
   return LS_OK;
 }
