@@ -119,18 +119,30 @@ k_gemm_mfma(const bf16* __restrict__ A, const bf16* __restrict__ W, int M, int N
   _Pragma("unroll") for (int i = 0; i < 4; ++i)                                                    \
     _Pragma("unroll") for (int j = 0; j < 2; ++j)                                                  \
       acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[set][i], bfr[set][j], acc[i][j], 0, 0, 0);
+  // within a k-step the six fragment reads of the next k-step are spread between the eight
+  // MFMAs (one read after each of the first six) instead of being issued as one burst
+#define LS_INTERLEAVE()                                                         \
+  _Pragma("unroll") for (int g_ = 0; g_ < 6; ++g_) {                            \
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0); /* one MFMA */           \
+    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0); /* one LDS read */       \
+  }                                                                             \
+  __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
 #define LS_COMPUTE_TILE(buf)                                    \
   {                                                             \
     bf16x8 af[2][4], bfr[2][2];                                 \
     LS_READ_FRAGS(buf, 0, 0)                                    \
+    __builtin_amdgcn_sched_barrier(0);                          \
     LS_READ_FRAGS(buf, 1, 1)                                    \
     LS_MFMA_STEP(0)                                             \
+    LS_INTERLEAVE()                                             \
     __builtin_amdgcn_sched_barrier(0);                          \
     LS_READ_FRAGS(buf, 2, 0)                                    \
     LS_MFMA_STEP(1)                                             \
+    LS_INTERLEAVE()                                             \
     __builtin_amdgcn_sched_barrier(0);                          \
     LS_READ_FRAGS(buf, 3, 1)                                    \
     LS_MFMA_STEP(0)                                             \
+    LS_INTERLEAVE()                                             \
     __builtin_amdgcn_sched_barrier(0);                          \
     LS_MFMA_STEP(1)                                             \
   }
@@ -150,6 +162,7 @@ k_gemm_mfma(const bf16* __restrict__ A, const bf16* __restrict__ W, int M, int N
   }
 #undef LS_FILL_TILE
 #undef LS_COMPUTE_TILE
+#undef LS_INTERLEAVE
 #undef LS_READ_FRAGS
 #undef LS_MFMA_STEP
 #undef LS_WAIT_FILLS
