@@ -23,19 +23,26 @@ namespace ls {
 
 namespace {
 
+// wavefronts per workgroup = context splits.  With one query head per kv head the kernel
+// needs few registers and 16 wavefronts with one load per operand in flight stream best
+// (measured inside the stage, 7B and 13B shapes); wider groups keep 8 wavefronts.
 #ifndef LS_ATTN_NW
 #define LS_ATTN_NW 8
 #endif
-#ifndef LS_ATTN_U
-#define LS_ATTN_U 2
+#ifndef LS_ATTN_NW1
+#define LS_ATTN_NW1 16
 #endif
-constexpr int NW = LS_ATTN_NW;  // wavefronts per workgroup = context splits
+#ifndef LS_ATTN_U
+#define LS_ATTN_U 1
+#endif
+constexpr int waves_for(int g) { return g == 1 ? LS_ATTN_NW1 : LS_ATTN_NW; }
 
 template <int HD, int G>
-__global__ void __launch_bounds__(NW * 64)
+__global__ void __launch_bounds__(waves_for(G) * 64)
 k_attn_decode(const bf16* __restrict__ qkv, int qkv_stride, const float2* __restrict__ cs,
               bf16* __restrict__ kc, bf16* __restrict__ vc, const int32_t* __restrict__ row_seq,
               const int32_t* __restrict__ row_pos, int hq, int hkv, int max_seq, bf16* __restrict__ out) {
+  constexpr int NW = waves_for(G);
   constexpr int LPK = HD / 8;     // lanes per key
   constexpr int KPI = 64 / LPK;   // keys per load instruction
   constexpr int U = (G >= 4) ? 2 : LS_ATTN_U;  // load instructions in flight per operand
@@ -206,7 +213,7 @@ template <int HD, int G>
 void launch_g(const void* qkv, int qkv_stride, const float* cs, void* kc, void* vc, const int32_t* row_seq,
               const int32_t* row_pos, int rows, int hkv, int max_seq, void* out, hipStream_t st) {
   dim3 grid(rows, hkv);
-  k_attn_decode<HD, G><<<grid, NW * 64, 0, st>>>((const bf16*)qkv, qkv_stride, (const float2*)cs, (bf16*)kc, (bf16*)vc,
+  k_attn_decode<HD, G><<<grid, waves_for(G) * 64, 0, st>>>((const bf16*)qkv, qkv_stride, (const float2*)cs, (bf16*)kc, (bf16*)vc,
                                                   row_seq, row_pos, hkv * G, hkv, max_seq, (bf16*)out);
 }
 
