@@ -60,3 +60,16 @@ def to_host(t):
 
 def rel_l2(got, want):
     return float(np.linalg.norm(np.asarray(got, np.float64) - want) / np.linalg.norm(want))
+
+
+def greedy_agreement(tok_gpu, logits_gpu, tok_ora, logits_ora):
+    """(raw matches, tie-adjusted matches, count)."""
+    err = np.abs(logits_gpu - logits_ora).max()
+    raw = adj = 0
+    for b in range(len(tok_ora)):
+        top2 = np.sort(logits_ora[b])[-2:]
+        tie = (top2[1] - top2[0]) < 4 * err
+        ok = int(tok_gpu[b]) == int(tok_ora[b])
+        raw += ok
+        adj += ok or tie
+    return raw, adj, len(tok_ora)

@@ -10,8 +10,7 @@ import numpy as np
 import pytest
 
 import synth
-from helpers import make_gpu, make_oracle, rel_l2, to_dev, to_host
-from test_gpu_parity import greedy_agreement
+from helpers import greedy_agreement, make_gpu, make_oracle, rel_l2, to_dev, to_host
 
 pytestmark = pytest.mark.gpu
 

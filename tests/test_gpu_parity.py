@@ -9,7 +9,7 @@ import numpy as np
 import pytest
 
 import synth
-from helpers import make_gpu, make_oracle, packed_blocks, rel_l2, to_dev, to_host
+from helpers import greedy_agreement, make_gpu, make_oracle, packed_blocks, rel_l2, to_dev, to_host
 
 pytestmark = pytest.mark.gpu
 
@@ -18,19 +18,6 @@ TOL = {"f32": 1e-4, "bf16": 2e-2}
 # a small bf16 decoder with grouped-query attention, several tiles wide plus ragged tails
 MINI_BF16 = synth.StageShape("bf16", 3, 512, 8, 2, 64, 1408, 1000)
 MINI_BF16_HD128 = synth.StageShape("bf16", 2, 768, 6, 6, 128, 2080, 0)
-
-
-def greedy_agreement(tok_gpu, logits_gpu, tok_ora, logits_ora):
-    """(raw matches, tie-adjusted matches, count)."""
-    err = np.abs(logits_gpu - logits_ora).max()
-    raw = adj = 0
-    for b in range(len(tok_ora)):
-        top2 = np.sort(logits_ora[b])[-2:]
-        tie = (top2[1] - top2[0]) < 4 * err
-        ok = int(tok_gpu[b]) == int(tok_ora[b])
-        raw += ok
-        adj += ok or tie
-    return raw, adj, len(tok_ora)
 
 
 def run_full_model(shape, seed, lengths, steps):

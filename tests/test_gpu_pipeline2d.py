@@ -7,7 +7,7 @@ import numpy as np
 import pytest
 
 import synth
-from helpers import make_gpu, make_oracle, rel_l2, to_dev, to_host
+from helpers import greedy_agreement, make_gpu, make_oracle, rel_l2, to_dev, to_host
 
 pytestmark = pytest.mark.gpu
 
@@ -84,8 +84,6 @@ def test_pipelined_microbatches_equal_serial_runs_and_the_oracle(cuts):
             assert torch.equal(got_k[m][s], ref_mbs[m].caches[s][0]), (m, s)
 
     # and against the oracle: whole model, teacher-forced with the pipeline's own tokens
-    from test_gpu_parity import greedy_agreement
-
     for m, lens in enumerate(lengths):
         ora = make_oracle(SHAPE, SEED, 0, SHAPE.n_layers_total, len(lens), max_s)
         nt, lg = ora.prefill(synth.token_ids(SEED + 1 + m, sum(lens), SHAPE.vocab), lens)
