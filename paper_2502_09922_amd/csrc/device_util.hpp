@@ -48,6 +48,20 @@ __device__ __forceinline__ float wave_max(float v) {
   return v;
 }
 
+// Sum over each aligned group of 16 lanes, every lane of the group gets the total.  Four
+// register-to-register DPP exchanges (lane^1, lane^2, mirrored half row, mirrored row) in a
+// fixed order -- no trip through the LDS crossbar as with a general shuffle.
+__device__ __forceinline__ float row16_sum(float v) {
+#define LS_DPP_ADD(ctrl) \
+  v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), ctrl, 0xF, 0xF, true))
+  LS_DPP_ADD(0xB1);   // quad_perm [1,0,3,2]
+  LS_DPP_ADD(0x4E);   // quad_perm [2,3,0,1]
+  LS_DPP_ADD(0x141);  // row_half_mirror: the other quad of the half row
+  LS_DPP_ADD(0x140);  // row_mirror: the other half row
+#undef LS_DPP_ADD
+  return v;
+}
+
 // silu(z) = z / (1 + exp(-z))
 __device__ __forceinline__ float silu_f(float z) { return z / (1.0f + __expf(-z)); }
 

@@ -19,9 +19,11 @@
 // Decode-step fusion of the RMSNorms (no separate norm launches):
 //   * a residual-add epilogue can also emit xb = bf16(x) and, per row and 16-column tile,
 //     the sum of squares of the new x (fp32, fixed-order reduction);
-//   * a NORM prologue takes that xb and those partial sums instead of a normalised input:
-//     the B operand is bf16(xb * gamma) (gamma staged per wave in LDS) and the accumulator
-//     is scaled by 1/sqrt(mean(x^2)+eps) of its row in the epilogue.
+//     the copy it emits is already multiplied by the gain of the norm that follows;
+//   * a NORM consumer takes that copy and those partial sums instead of a normalised input
+//     and scales the accumulator by 1/sqrt(mean(x^2)+eps) of its row in the epilogue.  The
+//     partial sums are requested before the weight stream is walked and only added up after
+//     it, so their latency hides behind the stream.
 #include "kernels.hpp"
 #include "device_util.hpp"
 
@@ -47,9 +49,6 @@ k_gemm_skinny(const bf16* __restrict__ X, const bf16* __restrict__ W, int M, int
   const int b0 = (int)((long)wave * nblk / KS), b1 = (int)((long)(wave + 1) * nblk / KS);
   const int nb = b1 - b0;
   unsigned char* scratch = smem + wave * (NW * 4096);
-  // NORM: this wave's slice of gamma lives behind the scratch areas of all waves
-  const int gam_stride = ((nblk + KS - 1) / KS + 1) * 256;
-  unsigned char* gam = smem + KS * (NW * 4096) + wave * gam_stride;
   // per-lane global offsets (elements) of the four load instructions of a block
   size_t woff[NW][4];
 #pragma unroll
@@ -90,42 +89,35 @@ k_gemm_skinny(const bf16* __restrict__ X, const bf16* __restrict__ W, int M, int
         wr[slot][s_][i_] = LS_STREAM_LOAD(reinterpret_cast<const u32x4*>(W + woff[s_][i_] + kb_)); \
   }
 
+  // NORM (<= 16 rows): wave w owns rows 4w..4w+3 of the 1/rms computation.  It requests their
+  // partial sums of squares straight into LDS (no registers held) BEFORE the weight ring:
+  // loads complete in order, so once the first weight block has arrived they are there too,
+  // and the wave turns them into 1/rms while the stream is in flight.
+  typedef __attribute__((address_space(3))) void lds_void;
+  const int pchunks = (fu.n_part + 63) >> 6;                          // 64-partial requests per row
+  float* ss_lds = reinterpret_cast<float*>(smem + KS * (NW * 4096));  // [M][pchunks * 64]
+  if constexpr (NORM && MT == 1) {
+    for (int c = 0; c < 4 * pchunks; ++c) {
+      const int row = wave * 4 + c / pchunks, idx = (c % pchunks) * 64 + lane;
+      if (row < M && idx < fu.n_part)
+        __builtin_amdgcn_global_load_lds((const void*)(fu.ss_in + (size_t)row * fu.n_part + idx),
+                                         (lds_void*)(ss_lds + (row * pchunks + c % pchunks) * 64), 4, 0, 0);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+  }
 #pragma unroll
   for (int p = 0; p < PF; ++p)
     if (p < nb) LS_LOAD_BLOCK(p, b0 + p)
 
   // residual epilogue: the element this thread will update is known now; fetch it while the
   // weights stream so that its latency is not added after the K-split reduction
-  float resid_pre = 0.f;
+  float resid_pre = 0.f, gain_pre = 1.f;  // gain_pre: the gain of this thread's column
   if constexpr (EPI == EPI_RESID) {
     const int e0 = threadIdx.x;
     if (e0 < MT * 256 && (e0 >> 8) * 16 + ((e0 >> 4) & 15) < M)
       resid_pre = resid[(size_t)((e0 >> 8) * 16 + ((e0 >> 4) & 15)) * N + n0 + (e0 & 15)];
+    if (fu.gamma_out) gain_pre = (float)fu.gamma_out[n0 + (threadIdx.x & 15)];
   }
-
-  // (after the weight ring has been requested, so the stream starts first)
-  if constexpr (NORM) {
-    for (int i = lane; i < nb * 16; i += 64)
-      *reinterpret_cast<u32x4*>(gam + i * 16) = *reinterpret_cast<const u32x4*>(fu.gamma + (size_t)b0 * 128 + i * 8);
-    // 1/rms per row: the waves share the rows; a row's partial sums of squares are read with
-    // independent loads (lane i takes partials i, i+64, ...), added in that order, then
-    // combined by the fixed lane butterfly
-    for (int row = wave; row < M; row += KS) {
-      float pv[8];
-#pragma unroll
-      for (int u = 0; u < 8; ++u) {
-        const int idx = lane + 64 * u;
-        pv[u] = idx < fu.n_part ? fu.ss_in[(size_t)row * fu.n_part + idx] : 0.f;
-      }
-      float ss = 0.f;
-#pragma unroll
-      for (int u = 0; u < 8; ++u) ss += pv[u];
-      for (int idx = lane + 512; idx < fu.n_part; idx += 64) ss += fu.ss_in[(size_t)row * fu.n_part + idx];
-      ss = wave_sum(ss);
-      if (lane == 0) sm_inv[row] = 1.0f / sqrtf(ss / (float)K + fu.eps);
-    }
-  }
-
 
   for (int b = 0; b < nb; b += PF) {
 #pragma unroll
@@ -144,18 +136,26 @@ k_gemm_skinny(const bf16* __restrict__ X, const bf16* __restrict__ W, int M, int
             const bf16x8 af = *reinterpret_cast<const bf16x8*>(scratch + s * 4096 + a_off[kk]);
 #pragma unroll
             for (int t = 0; t < MT; ++t) {
-              bf16x8 xf = __builtin_bit_cast(bf16x8, xr[sl][t][kk]);
-              if constexpr (NORM) {
-                const bf16x8 g8 = *reinterpret_cast<const bf16x8*>(gam + ((b + sl) * 128 + kk * 32 + lg * 8) * 2);
-#pragma unroll
-                for (int e = 0; e < 8; ++e) xf[e] = (bf16)((float)xf[e] * (float)g8[e]);
-              }
+              const bf16x8 xf = __builtin_bit_cast(bf16x8, xr[sl][t][kk]);
               acc[s][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af, xf, acc[s][t], 0, 0, 0);
             }
           }
         }
         // refill this ring slot with the block PF ahead
         if (b + sl + PF < nb) LS_LOAD_BLOCK(sl, b0 + b + sl + PF)
+        if constexpr (NORM && MT == 1) {
+          if (sl == 0 && b == 0) {
+            __builtin_amdgcn_sched_barrier(0);  // stay behind the wait for the first weight block
+            // the first weight block has arrived, hence this wave's partial sums too: 16 lanes
+            // share a row, a lane adds every 16th partial in index order, then the fixed exchange
+            const int row = wave * 4 + (lane >> 4);
+            float ss = 0.f;
+            if (row < M)
+              for (int idx = lane & 15; idx < fu.n_part; idx += 16) ss += ss_lds[row * (pchunks * 64) + idx];
+            ss = row16_sum(ss);
+            if (row < M && (lane & 15) == 0) sm_inv[row] = 1.0f / sqrtf(ss / (float)K + fu.eps);
+          }
+        }
       }
     }
   }
@@ -163,6 +163,15 @@ k_gemm_skinny(const bf16* __restrict__ X, const bf16* __restrict__ W, int M, int
 
   // ---- sum the KS partial tiles in wave order, then the epilogue
   __syncthreads();  // every wave is done with its scratch; reuse LDS for the partials
+  if constexpr (NORM && MT > 1) {
+    // more than 16 rows: 1/rms per row straight from the partial sums in global memory
+    for (int row = threadIdx.x >> 4; row < M; row += KS * 4) {
+      float ss = 0.f;
+      for (int idx = threadIdx.x & 15; idx < fu.n_part; idx += 16) ss += fu.ss_in[(size_t)row * fu.n_part + idx];
+      ss = row16_sum(ss);
+      if ((threadIdx.x & 15) == 0) sm_inv[row] = 1.0f / sqrtf(ss / (float)K + fu.eps);
+    }
+  }
   float* red = reinterpret_cast<float*>(smem);  // [KS][NW][MT][16 m][16 n]
 #pragma unroll
   for (int s = 0; s < NW; ++s)
@@ -189,10 +198,8 @@ k_gemm_skinny(const bf16* __restrict__ X, const bf16* __restrict__ W, int M, int
       const float xn = (e == (int)threadIdx.x ? resid_pre : resid[o]) + v[0];
       resid[o] = xn;
       if (fu.xb_out) {
-        fu.xb_out[o] = (bf16)xn;
-        float ss = xn * xn;  // sum over the 16 columns of this tile, fixed butterfly
-#pragma unroll
-        for (int off = 8; off; off >>= 1) ss += __shfl_xor(ss, off);
+        fu.xb_out[o] = (bf16)(xn * gain_pre);  // n == threadIdx.x % 16 in every pass of this loop
+        const float ss = row16_sum(xn * xn);  // over the 16 columns of this tile, fixed order
         if (n == 0) fu.ss_out[(size_t)m * (N >> 4) + blockIdx.x] = ss;
       }
     }
@@ -211,9 +218,11 @@ void launch_kn(const void* X, const void* W, int M, int N, int K, void* out, flo
   // register ring depth in 128-wide K blocks; two blocks measured best for every shape
   // (a deeper ring costs registers, hence resident wavefronts)
   constexpr int PF = LS_SKINNY_PF ? LS_SKINNY_PF : 2;
-  const int gam_bytes = NORM ? KS * (((K / 128 + KS - 1) / KS + 1) * 256) : 0;
-  const int scratch = KS * NW * 4096 + gam_bytes, red = KS * NW * MT * 1024;
-  const int smem = scratch > red ? scratch : red;
+  // the K-split partial tiles reuse the scratch areas (KS*NW*MT KB <= KS*NW*4 KB); a NORM
+  // kernel for <= 16 rows keeps the rows' partial sums of squares behind them
+  const int scratch = KS * NW * 4096;
+  const int ss_bytes = (NORM && MT == 1) ? M * ((fu.n_part + 63) / 64) * 256 : 0;
+  const int smem = scratch + ss_bytes;
   static int attr_bytes = 0;
   if (smem > attr_bytes) {
     (void)hipFuncSetAttribute((const void*)k_gemm_skinny<MT, EPI, KS, PF, NORM>, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
@@ -227,7 +236,7 @@ template <int MT, int EPI, int KS>
 void launch_k(const void* X, const void* W, int M, int N, int K, void* out, float* resid, const SkinnyFusion& fu,
               hipStream_t st) {
   if constexpr (EPI == EPI_STORE || EPI == EPI_SWIGLU) {
-    if (fu.gamma) { launch_kn<MT, EPI, KS, true>(X, W, M, N, K, out, resid, fu, st); return; }
+    if (fu.ss_in) { launch_kn<MT, EPI, KS, true>(X, W, M, N, K, out, resid, fu, st); return; }
   }
   launch_kn<MT, EPI, KS, false>(X, W, M, N, K, out, resid, fu, st);
 }

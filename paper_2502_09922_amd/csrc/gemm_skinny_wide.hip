@@ -6,7 +6,7 @@
 //   * a 256-thread workgroup owns 64 output columns, 16 per wavefront (with SwiGLU: 16 gate
 //     rows + 16 up rows per wavefront), and all four wavefronts walk the SAME K range;
 //   * the X block of a K step (M rows x 256 bytes) is fetched once per workgroup with fully
-//     coalesced 16-byte loads, optionally multiplied by the RMSNorm gain, and staged in LDS
+//     coalesced 16-byte loads and staged in LDS
 //     (double buffered, chunks XOR-swizzled by row) in the layout an MFMA B operand reads;
 //   * W streams exactly as in the narrow kernel: 4 loads of 16 rows x 256 contiguous bytes per
 //     wavefront and K step, a register ring two steps deep, a wave-private LDS transpose;
@@ -24,10 +24,10 @@ namespace {
 
 constexpr int WAVES = 4;
 
-template <int MT, bool GLU, bool NORM>
+template <int MT, bool GLU>
 __global__ void __launch_bounds__(WAVES * 64)
 k_gemm_wide(const bf16* __restrict__ X, const bf16* __restrict__ W, int M, int N, int K,
-            float* __restrict__ part, const bf16* __restrict__ gamma, int blocks_per_split) {
+            float* __restrict__ part, int blocks_per_split) {
   constexpr int NW = GLU ? 2 : 1;
   constexpr int PF = 2;
   constexpr int XS_BYTES = MT * 16 * 256;  // one staged X block
@@ -64,7 +64,7 @@ k_gemm_wide(const bf16* __restrict__ X, const bf16* __restrict__ W, int M, int N
   }
 
   u32x4 wr[PF][NW][4];
-  u32x4 xg[MT], gg;
+  u32x4 xg[MT];
   f32x4 acc[NW][MT];
 #pragma unroll
   for (int s = 0; s < NW; ++s)
@@ -83,18 +83,10 @@ k_gemm_wide(const bf16* __restrict__ X, const bf16* __restrict__ W, int M, int N
     const size_t kb_ = (size_t)(blk) << 7;                                             \
     _Pragma("unroll") for (int i_ = 0; i_ < MT; ++i_)                                  \
       xg[i_] = *reinterpret_cast<const u32x4*>(X + xoff[i_] + kb_);                    \
-    if constexpr (NORM) gg = *reinterpret_cast<const u32x4*>(gamma + kb_ + (xc << 3)); \
   }
 #define LS_STORE_X(buf)                                                                \
-  _Pragma("unroll") for (int i_ = 0; i_ < MT; ++i_) {                                  \
-    bf16x8 v_ = __builtin_bit_cast(bf16x8, xg[i_]);                                    \
-    if constexpr (NORM) {                                                              \
-      const bf16x8 g_ = __builtin_bit_cast(bf16x8, gg);                                \
-      _Pragma("unroll") for (int e_ = 0; e_ < 8; ++e_)                                 \
-        v_[e_] = (bf16)((float)v_[e_] * (float)g_[e_]);                                \
-    }                                                                                  \
-    *reinterpret_cast<bf16x8*>(xs + (buf) * XS_BYTES + xs_off[i_]) = v_;               \
-  }
+  _Pragma("unroll") for (int i_ = 0; i_ < MT; ++i_)                                    \
+    *reinterpret_cast<u32x4*>(xs + (buf) * XS_BYTES + xs_off[i_]) = xg[i_];
   // one K step with ring slot `slot`
 #define LS_STEP(slot, b)                                                                        \
   {                                                                                             \
@@ -177,10 +169,8 @@ k_wide_finish(const float* __restrict__ part, int splits, int M, int N, int K, v
     const float xn = resid[o] + v[0];
     resid[o] = xn;
     if (fu.xb_out) {
-      fu.xb_out[o] = (bf16)xn;
-      float ss = xn * xn;
-#pragma unroll
-      for (int off = 8; off; off >>= 1) ss += __shfl_xor(ss, off);
+      fu.xb_out[o] = (bf16)(fu.gamma_out ? xn * (float)fu.gamma_out[n] : xn);
+      const float ss = row16_sum(xn * xn);
       if ((n & 15) == 0) fu.ss_out[(size_t)m * (N >> 4) + (n >> 4)] = ss;
     }
   }
@@ -188,32 +178,30 @@ k_wide_finish(const float* __restrict__ part, int splits, int M, int N, int K, v
   else ((float*)outv)[o] = v[0];
 }
 
-template <int MT, bool GLU, bool NORM>
-void launch_main(const void* X, const void* W, int M, int N, int K, float* part, const bf16* gamma, int splits,
-                 int bps, hipStream_t st) {
+template <int MT, bool GLU>
+void launch_main(const void* X, const void* W, int M, int N, int K, float* part, int splits, int bps, hipStream_t st) {
   constexpr int NW = GLU ? 2 : 1;
   constexpr int smem = 2 * MT * 16 * 256 + WAVES * NW * 4096;
   static bool attr_set = false;
   if (!attr_set) {
-    (void)hipFuncSetAttribute((const void*)k_gemm_wide<MT, GLU, NORM>, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    (void)hipFuncSetAttribute((const void*)k_gemm_wide<MT, GLU>, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
     attr_set = true;
   }
   dim3 grid(N / 64, splits);
-  k_gemm_wide<MT, GLU, NORM><<<grid, WAVES * 64, smem, st>>>((const bf16*)X, (const bf16*)W, M, N, K, part, gamma, bps);
+  k_gemm_wide<MT, GLU><<<grid, WAVES * 64, smem, st>>>((const bf16*)X, (const bf16*)W, M, N, K, part, bps);
 }
 
-template <bool GLU, bool NORM>
-void launch_mt(const void* X, const void* W, int M, int N, int K, float* part, const bf16* gamma, int splits, int bps,
-               hipStream_t st) {
-  if (M <= 32) launch_main<2, GLU, NORM>(X, W, M, N, K, part, gamma, splits, bps, st);
-  else launch_main<4, GLU, NORM>(X, W, M, N, K, part, gamma, splits, bps, st);
+template <bool GLU>
+void launch_mt(const void* X, const void* W, int M, int N, int K, float* part, int splits, int bps, hipStream_t st) {
+  if (M <= 32) launch_main<2, GLU>(X, W, M, N, K, part, splits, bps, st);
+  else launch_main<4, GLU>(X, W, M, N, K, part, splits, bps, st);
 }
 
 template <int EPI>
 void launch_finish(const float* part, int splits, int M, int N, int K, void* out, float* resid,
                    const SkinnyFusion& fu, hipStream_t st) {
   dim3 grid((N + 255) / 256, M);
-  if (fu.gamma) k_wide_finish<EPI, true><<<grid, 256, 0, st>>>(part, splits, M, N, K, out, resid, fu);
+  if (fu.ss_in) k_wide_finish<EPI, true><<<grid, 256, 0, st>>>(part, splits, M, N, K, out, resid, fu);
   else k_wide_finish<EPI, false><<<grid, 256, 0, st>>>(part, splits, M, N, K, out, resid, fu);
 }
 
@@ -240,14 +228,8 @@ void launch_gemm_wide(Epilogue epi, const void* X, const void* W, int M, int N, 
   const SkinnyFusion fu = fusion ? *fusion : SkinnyFusion{};
   const int splits = gemm_wide_splits(N, K);
   const int nblk = K / 128, bps = (nblk + splits - 1) / splits;
-  const bool glu = epi == EPI_SWIGLU, norm = fu.gamma != nullptr;
-  if (glu) {
-    if (norm) launch_mt<true, true>(X, W, M, N, K, splitk_ws, fu.gamma, splits, bps, st);
-    else launch_mt<true, false>(X, W, M, N, K, splitk_ws, fu.gamma, splits, bps, st);
-  } else {
-    if (norm) launch_mt<false, true>(X, W, M, N, K, splitk_ws, fu.gamma, splits, bps, st);
-    else launch_mt<false, false>(X, W, M, N, K, splitk_ws, fu.gamma, splits, bps, st);
-  }
+  if (epi == EPI_SWIGLU) launch_mt<true>(X, W, M, N, K, splitk_ws, splits, bps, st);
+  else launch_mt<false>(X, W, M, N, K, splitk_ws, splits, bps, st);
   switch (epi) {
     case EPI_STORE: launch_finish<EPI_STORE>(splitk_ws, splits, M, N, K, out, resid, fu, st); break;
     case EPI_RESID: launch_finish<EPI_RESID>(splitk_ws, splits, M, N, K, out, resid, fu, st); break;

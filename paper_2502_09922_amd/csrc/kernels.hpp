@@ -39,11 +39,12 @@ void launch_seq_lens_set(const int32_t* cu_seqlens, int batch, int32_t* seq_lens
 void launch_seq_lens_inc(int batch, int max_seq, int32_t* seq_lens, hipStream_t st);
 
 // Decode step, fused path: row maps + seq_lens increment + fp32 residual rows + their
-// storage-type copy xb + per-16-column sums of squares ss_part[batch][d/16], one launch.
+// storage-type copy xb (times a gain) + per-16-column sums of squares ss_part[batch][d/16], one launch.
 // table != nullptr: `in` holds int32 token ids and rows are gathered from the table.
+// xb = storage-type copy of the rows times gamma (the gain of the first norm; nullptr: none).
 void launch_decode_prologue(uint32_t dt, const void* table, const void* in, int32_t* seq_lens, int batch, int max_seq,
                             int d, int vocab, int32_t* row_seq, int32_t* row_pos, int32_t* last_rows, float* x,
-                            void* xb, float* ss_part, hipStream_t st);
+                            void* xb, float* ss_part, const void* gamma, hipStream_t st);
 
 void launch_embed(uint32_t dt, const void* table, const int32_t* tok, float* x, int rows, int d,
                   int vocab, hipStream_t st);
@@ -81,18 +82,21 @@ void launch_gemm_mfma(Epilogue epi, const void* A, const void* W, int M, int N, 
 
 // bf16 weight-streaming kernel for decode steps (M <= 64); needs N % 16 == 0, K % 128 == 0.
 // ks = wavefronts that split K inside a workgroup (4, 8, 16), 0 = chosen from the shape.
-// Optional RMSNorm fusion of the decode step (all pointers device memory):
-//   gamma != nullptr (EPI_STORE / EPI_SWIGLU): X is xb = bf16(x), un-normalised; the kernel
-//     multiplies by gamma[K] and by 1/sqrt(sum(ss_in[row][0..n_part)) / K + eps).
-//   xb_out != nullptr (EPI_RESID): also write bf16 of the updated residual rows to xb_out[M,N]
-//     and each row's sum of squares per 16-column tile to ss_out[M][N/16].
+// Optional RMSNorm fusion of the decode step (all pointers device memory).  The gain of a
+// norm is applied by whoever PRODUCES the bf16 copy of the residual rows, the row scale by
+// the GEMM that CONSUMES it:
+//   xb_out != nullptr (EPI_RESID): also write xb_out[M,N] = bf16(x_new * gamma_out[n])
+//     (gamma_out == nullptr: no gain) and each row's sum of squares of x_new per 16-column
+//     tile to ss_out[M][N/16].
+//   ss_in != nullptr (EPI_STORE / EPI_SWIGLU): X is such a copy; the accumulator is scaled
+//     by 1/sqrt(sum(ss_in[row][0..n_part)) / K + eps) of its row in the epilogue.
 struct SkinnyFusion {
-  const __bf16* gamma = nullptr;
   const float* ss_in = nullptr;
   int n_part = 0;
   float eps = 0.f;
   __bf16* xb_out = nullptr;
   float* ss_out = nullptr;
+  const __bf16* gamma_out = nullptr;
 };
 bool gemm_skinny_supported(int M, int N, int K);
 void launch_gemm_skinny(Epilogue epi, const void* X, const void* W, int M, int N, int K, void* out, float* resid,

@@ -50,7 +50,7 @@ __global__ void __launch_bounds__(256) k_decode_prologue(const T* __restrict__ t
                                                          int32_t* seq_lens, int max_seq, int d, int vocab,
                                                          int32_t* row_seq, int32_t* row_pos, int32_t* last_rows,
                                                          float* __restrict__ x, T* __restrict__ xb,
-                                                         float* __restrict__ ss_part) {
+                                                         float* __restrict__ ss_part, const T* __restrict__ gamma) {
   const int b = blockIdx.x;
   if (threadIdx.x == 0) {
     const int p = seq_lens[b];
@@ -75,7 +75,7 @@ __global__ void __launch_bounds__(256) k_decode_prologue(const T* __restrict__ t
       const T raw = src[tile * 16 + e];
       const float v = to_f(raw);
       x[(size_t)b * d + tile * 16 + e] = v;
-      xb[(size_t)b * d + tile * 16 + e] = raw;
+      xb[(size_t)b * d + tile * 16 + e] = gamma ? from_f<T>(v * to_f(gamma[tile * 16 + e])) : raw;
       ss += v * v;
     }
     ss_part[(size_t)b * (d >> 4) + tile] = ss;
@@ -84,13 +84,13 @@ __global__ void __launch_bounds__(256) k_decode_prologue(const T* __restrict__ t
 
 void launch_decode_prologue(uint32_t dt, const void* table, const void* in, int32_t* seq_lens, int batch, int max_seq,
                             int d, int vocab, int32_t* row_seq, int32_t* row_pos, int32_t* last_rows, float* x,
-                            void* xb, float* ss_part, hipStream_t st) {
+                            void* xb, float* ss_part, const void* gamma, hipStream_t st) {
   if (dt == F32)
     k_decode_prologue<float><<<batch, 256, 0, st>>>((const float*)table, in, seq_lens, max_seq, d, vocab, row_seq,
-                                                    row_pos, last_rows, x, (float*)xb, ss_part);
+                                                    row_pos, last_rows, x, (float*)xb, ss_part, (const float*)gamma);
   else
     k_decode_prologue<bf16><<<batch, 256, 0, st>>>((const bf16*)table, in, seq_lens, max_seq, d, vocab, row_seq,
-                                                   row_pos, last_rows, x, (bf16*)xb, ss_part);
+                                                   row_pos, last_rows, x, (bf16*)xb, ss_part, (const bf16*)gamma);
 }
 
 void launch_row_index_prefill(const int32_t* cu, int batch, int total, int32_t* row_seq,

@@ -488,9 +488,20 @@ ls_status forward(ls_stage* s, bool prefill, const void* in, const int32_t* cu_d
       LS_HIP(hipStreamWaitEvent(st, eb->loaded, 0));
       table = s->slab + eb->off;
     }
-    launch_decode_prologue(dt, table, in, kv->seq_lens, batch, c.max_seq, d, c.vocab, row_seq, row_pos, last_rows, x,
-                           xb, ss_a, st);
     const int n_layers = s->hi - s->lo;
+    // The gain of a norm is applied where the bf16 copy of the residual rows is written: by
+    // the prologue (first layer's attention norm), by the O projection (the same layer's FFN
+    // norm) and by the down projection (the NEXT layer's attention norm -- so a layer's last
+    // kernel is also ordered after the next layer's block).
+    auto gain = [&](int li, int tensor) {
+      const Block& b = s->blocks[s->layer0 + li];
+      TensorSpan sp[6];
+      block_tensors(&c, b.layer, sp, nullptr);
+      return (const __bf16*)(s->slab + b.off + sp[tensor].off);
+    };
+    LS_HIP(hipStreamWaitEvent(st, s->blocks[s->layer0].loaded, 0));  // the gate of the first layer
+    launch_decode_prologue(dt, table, in, kv->seq_lens, batch, c.max_seq, d, c.vocab, row_seq, row_pos, last_rows, x,
+                           xb, ss_a, gain(0, 0), st);
     for (int li = 0; li < n_layers; ++li) {
       const Block& b = s->blocks[s->layer0 + li];
       TensorSpan sp[6];
@@ -499,17 +510,20 @@ ls_status forward(ls_stage* s, bool prefill, const void* in, const int32_t* cu_d
       LS_HIP(hipStreamWaitEvent(st, b.loaded, 0));  // the gate
       char* kc = (char*)kv->k + li * kv_layer;
       char* vc = (char*)kv->v + li * kv_layer;
+      const bool more = li + 1 < n_layers;
       SkinnyFusion f_qkv, f_o, f_gu, f_dn;
-      f_qkv.gamma = (const __bf16*)(base + sp[0].off); f_qkv.ss_in = ss_a; f_qkv.n_part = d / 16; f_qkv.eps = c.rms_eps;
-      f_o.xb_out = xb2; f_o.ss_out = ss_b;
-      f_gu.gamma = (const __bf16*)(base + sp[3].off); f_gu.ss_in = ss_b; f_gu.n_part = d / 16; f_gu.eps = c.rms_eps;
-      // the last layer of a middle stage writes the stage output directly
-      f_dn.xb_out = (li == n_layers - 1 && !s->last) ? (__bf16*)out : xb; f_dn.ss_out = ss_a;
+      f_qkv.ss_in = ss_a; f_qkv.n_part = d / 16; f_qkv.eps = c.rms_eps;
+      f_o.xb_out = xb2; f_o.ss_out = ss_b; f_o.gamma_out = gain(li, 3);
+      f_gu.ss_in = ss_b; f_gu.n_part = d / 16; f_gu.eps = c.rms_eps;
+      // the last layer of a middle stage writes the stage output directly (no gain)
+      f_dn.xb_out = (!more && !s->last) ? (__bf16*)out : xb; f_dn.ss_out = ss_a;
+      f_dn.gamma_out = more ? gain(li + 1, 0) : nullptr;
       PROBE(LS_OP_GEMM_QKV, launch_gemm(dt, EPI_STORE, xb, base + sp[1].off, rows, qkv_cols, d, qkv, nullptr, st, &gsc, &f_qkv));
       PROBE(LS_OP_ATTENTION, launch_attention_block(dt, nullptr, batch, 1, qkv, cs, kc, vc, row_seq, row_pos, rows, hq,
                                                     hkv, hd, c.max_seq, attn, st));
       PROBE(LS_OP_GEMM_O, launch_gemm(dt, EPI_RESID, attn, base + sp[2].off, rows, d, hq * hd, nullptr, x, st, &gsc, &f_o));
       PROBE(LS_OP_GEMM_GATEUP, launch_gemm(dt, EPI_SWIGLU, xb2, base + sp[4].off, rows, F, d, hbuf, nullptr, st, &gsc, &f_gu));
+      if (more) LS_HIP(hipStreamWaitEvent(st, s->blocks[s->layer0 + li + 1].loaded, 0));  // its gain is read next
       PROBE(LS_OP_GEMM_DOWN, launch_gemm(dt, EPI_RESID, hbuf, base + sp[5].off, rows, d, F, nullptr, x, st, &gsc, &f_dn));
     }
     if (s->last) {
