@@ -146,6 +146,25 @@ k_wide_finish(const float* __restrict__ part, int splits, int M, int N, int K, v
   constexpr int NW = (EPI == EPI_SWIGLU) ? 2 : 1;
   __shared__ float wsum[4];
   const int m = blockIdx.y, n = blockIdx.x * 256 + threadIdx.x;
+  // everything this thread needs from global memory is requested before the row's 1/rms is
+  // worked out, so the two latencies overlap
+  const bool live = n < N;  // N % 16 == 0: 16-lane groups are live or not together
+  const size_t o = (size_t)m * N + (live ? n : 0);
+  float v[NW];
+#pragma unroll
+  for (int s = 0; s < NW; ++s) {
+    float sum = 0.f;
+    if (live)
+      for (int sp = 0; sp < splits; ++sp) sum += part[(((size_t)sp * NW + s) * M + m) * N + n];
+    v[s] = sum;
+  }
+  float x_old = 0.f, gain = 1.f;
+  if constexpr (EPI == EPI_RESID) {
+    if (live) {
+      x_old = resid[o];
+      if (fu.gamma_out) gain = (float)fu.gamma_out[n];
+    }
+  }
   float inv = 1.f;
   if constexpr (NORM) {
     float ss = 0.f;
@@ -155,21 +174,15 @@ k_wide_finish(const float* __restrict__ part, int splits, int M, int N, int K, v
     __syncthreads();
     inv = 1.0f / sqrtf(((wsum[0] + wsum[1]) + (wsum[2] + wsum[3])) / (float)K + fu.eps);
   }
-  if (n >= N) return;  // N % 16 == 0: 16-lane groups leave together
-  float v[NW];
+  if (!live) return;
 #pragma unroll
-  for (int s = 0; s < NW; ++s) {
-    float sum = 0.f;
-    for (int sp = 0; sp < splits; ++sp) sum += part[(((size_t)sp * NW + s) * M + m) * N + n];
-    v[s] = sum * inv;
-  }
-  const size_t o = (size_t)m * N + n;
+  for (int s = 0; s < NW; ++s) v[s] *= inv;
   if constexpr (EPI == EPI_STORE) ((bf16*)outv)[o] = (bf16)v[0];
   else if constexpr (EPI == EPI_RESID) {
-    const float xn = resid[o] + v[0];
+    const float xn = x_old + v[0];
     resid[o] = xn;
     if (fu.xb_out) {
-      fu.xb_out[o] = (bf16)(fu.gamma_out ? xn * (float)fu.gamma_out[n] : xn);
+      fu.xb_out[o] = (bf16)(xn * gain);
       const float ss = row16_sum(xn * xn);
       if ((n & 15) == 0) fu.ss_out[(size_t)m * (N >> 4) + (n >> 4)] = ss;
     }

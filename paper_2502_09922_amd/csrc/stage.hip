@@ -150,7 +150,22 @@ struct Block {
   int state;
   bool timed;  // copy_start / loaded bracket a copy made with profiling on
   hipEvent_t copy_start, loaded;
+  // the host has seen `loaded` complete since the block was enqueued: the bytes are in HBM for
+  // all work enqueued from now on, on any stream, and the gate needs no event wait any more
+  bool landed;
 };
+
+// The gate: order stream `st` after the block's copy (nothing to enqueue once the copy is
+// known to have completed).
+inline hipError_t gate(Block& b, hipStream_t st) {
+  if (b.landed) return hipSuccess;
+  if (hipEventQuery(b.loaded) == hipSuccess) {
+    b.landed = true;
+    return hipSuccess;
+  }
+  (void)hipGetLastError();  // hipErrorNotReady from the query is not an error
+  return hipStreamWaitEvent(st, b.loaded, 0);
+}
 
 }  // namespace
 
@@ -363,6 +378,7 @@ ls_status ls_stage_load_block(ls_stage* s, const void* host_ptr, int layer, void
   LS_HIP(hipMemcpyAsync(s->slab + b->off, host_ptr, b->bytes, hipMemcpyHostToDevice, st));
   LS_HIP(hipEventRecord(b->loaded, st));
   b->state = ENQUEUED;
+  b->landed = false;
   return LS_OK;
 }
 
@@ -388,6 +404,7 @@ ls_status ls_stage_load_layers(ls_stage* s, const void* host_ptr, int first, int
     b->timed = s->profiling;
     LS_HIP(hipEventRecord(b->loaded, st));
     b->state = ENQUEUED;
+    b->landed = false;
   }
   return LS_OK;
 }
@@ -400,6 +417,7 @@ ls_status ls_stage_adopt_block(ls_stage* s, int layer, void* hip_stream) {
   b->timed = false;
   LS_HIP(hipEventRecord(b->loaded, (hipStream_t)hip_stream));
   b->state = ENQUEUED;
+  b->landed = false;
   return LS_OK;
 }
 
@@ -408,6 +426,7 @@ ls_status ls_stage_reset_blocks(ls_stage* s) {
   for (auto& b : s->blocks) {
     b.state = NOT_LOADED;
     b.timed = false;
+    b.landed = false;
   }
   s->origin_block = -1;
   return LS_OK;
@@ -484,8 +503,8 @@ ls_status forward(ls_stage* s, bool prefill, const void* in, const int32_t* cu_d
     float* ss_b = (float*)(ws + s->w.ss_b);
     const void* table = nullptr;
     if (s->first) {
-      const Block* eb = s->find(LS_BLOCK_EMBED);
-      LS_HIP(hipStreamWaitEvent(st, eb->loaded, 0));
+      Block* eb = s->find(LS_BLOCK_EMBED);
+      LS_HIP(gate(*eb, st));
       table = s->slab + eb->off;
     }
     const int n_layers = s->hi - s->lo;
@@ -499,15 +518,15 @@ ls_status forward(ls_stage* s, bool prefill, const void* in, const int32_t* cu_d
       block_tensors(&c, b.layer, sp, nullptr);
       return (const __bf16*)(s->slab + b.off + sp[tensor].off);
     };
-    LS_HIP(hipStreamWaitEvent(st, s->blocks[s->layer0].loaded, 0));  // the gate of the first layer
+    LS_HIP(gate(s->blocks[s->layer0], st));  // the gate of the first layer
     launch_decode_prologue(dt, table, in, kv->seq_lens, batch, c.max_seq, d, c.vocab, row_seq, row_pos, last_rows, x,
                            xb, ss_a, gain(0, 0), st);
     for (int li = 0; li < n_layers; ++li) {
-      const Block& b = s->blocks[s->layer0 + li];
+      Block& b = s->blocks[s->layer0 + li];
       TensorSpan sp[6];
       block_tensors(&c, b.layer, sp, nullptr);
       const char* base = s->slab + b.off;
-      LS_HIP(hipStreamWaitEvent(st, b.loaded, 0));  // the gate
+      LS_HIP(gate(b, st));  // the gate
       char* kc = (char*)kv->k + li * kv_layer;
       char* vc = (char*)kv->v + li * kv_layer;
       const bool more = li + 1 < n_layers;
@@ -523,15 +542,15 @@ ls_status forward(ls_stage* s, bool prefill, const void* in, const int32_t* cu_d
                                                     hkv, hd, c.max_seq, attn, st));
       PROBE(LS_OP_GEMM_O, launch_gemm(dt, EPI_RESID, attn, base + sp[2].off, rows, d, hq * hd, nullptr, x, st, &gsc, &f_o));
       PROBE(LS_OP_GEMM_GATEUP, launch_gemm(dt, EPI_SWIGLU, xb2, base + sp[4].off, rows, F, d, hbuf, nullptr, st, &gsc, &f_gu));
-      if (more) LS_HIP(hipStreamWaitEvent(st, s->blocks[s->layer0 + li + 1].loaded, 0));  // its gain is read next
+      if (more) LS_HIP(gate(s->blocks[s->layer0 + li + 1], st));  // its gain is read next
       PROBE(LS_OP_GEMM_DOWN, launch_gemm(dt, EPI_RESID, hbuf, base + sp[5].off, rows, d, F, nullptr, x, st, &gsc, &f_dn));
     }
     if (s->last) {
-      const Block* hb = s->find(s->hi);
+      Block* hb = s->find(s->hi);
       TensorSpan sp[6];
       block_tensors(&c, hb->layer, sp, nullptr);
       const char* base = s->slab + hb->off;
-      LS_HIP(hipStreamWaitEvent(st, hb->loaded, 0));
+      LS_HIP(gate(*hb, st));
       float* logits = logits_out ? logits_out : (float*)(ws + s->w.logits);
       launch_rmsnorm(dt, x, base + sp[0].off, y, batch, d, c.rms_eps, last_rows, st);
       launch_gemm(dt, EPI_F32, y, base + sp[1].off, batch, c.vocab, d, logits, nullptr, st, &gsc);
@@ -545,20 +564,20 @@ ls_status forward(ls_stage* s, bool prefill, const void* in, const int32_t* cu_d
   else launch_row_index_decode(kv->seq_lens, batch, c.max_seq, row_seq, row_pos, last_rows, st);
 
   if (s->first) {
-    const Block* eb = s->find(LS_BLOCK_EMBED);
-    LS_HIP(hipStreamWaitEvent(st, eb->loaded, 0));  // gate: embedding block has landed
+    Block* eb = s->find(LS_BLOCK_EMBED);
+    LS_HIP(gate(*eb, st));  // gate: embedding block has landed
     launch_embed(dt, s->slab + eb->off, (const int32_t*)in, x, rows, d, c.vocab, st);
   } else {
     launch_load_hidden(dt, in, x, (size_t)rows * d, st);
   }
 
   for (int li = 0; li < s->hi - s->lo; ++li) {
-    const Block& b = s->blocks[s->layer0 + li];
+    Block& b = s->blocks[s->layer0 + li];
     TensorSpan sp[6];
     block_tensors(&c, b.layer, sp, nullptr);
     const char* base = s->slab + b.off;
     // the gate: nothing of this layer may read its weights before its block has landed
-    LS_HIP(hipStreamWaitEvent(st, b.loaded, 0));
+    LS_HIP(gate(b, st));
     if (timed) LS_HIP(hipEventRecord(s->comp_start[li], st));
     char* kc = (char*)kv->k + li * kv_layer;
     char* vc = (char*)kv->v + li * kv_layer;
@@ -577,11 +596,11 @@ ls_status forward(ls_stage* s, bool prefill, const void* in, const int32_t* cu_d
   if (timed) s->compute_timed = true;
 
   if (s->last) {
-    const Block* hb = s->find(s->hi);
+    Block* hb = s->find(s->hi);
     TensorSpan sp[6];
     block_tensors(&c, hb->layer, sp, nullptr);
     const char* base = s->slab + hb->off;
-    LS_HIP(hipStreamWaitEvent(st, hb->loaded, 0));  // gate: head block has landed
+    LS_HIP(gate(*hb, st));  // gate: head block has landed
     float* logits = logits_out ? logits_out : (float*)(ws + s->w.logits);
     launch_rmsnorm(dt, x, base + sp[0].off, y, batch, d, c.rms_eps, last_rows, st);
     launch_gemm(dt, EPI_F32, y, base + sp[1].off, batch, c.vocab, d, logits, nullptr, st, &gsc);
