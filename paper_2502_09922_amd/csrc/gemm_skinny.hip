@@ -90,18 +90,24 @@ k_gemm_skinny(const bf16* __restrict__ X, const bf16* __restrict__ W, int M, int
   }
 
   // NORM (<= 16 rows): wave w owns rows 4w..4w+3 of the 1/rms computation.  It requests their
-  // partial sums of squares straight into LDS (no registers held) BEFORE the weight ring:
-  // loads complete in order, so once the first weight block has arrived they are there too,
-  // and the wave turns them into 1/rms while the stream is in flight.
+  // partial sums of squares straight into LDS (no registers held) BEFORE the weight ring, 16
+  // bytes per lane, so one request covers 256 partials of a row (K is a multiple of 128, so a
+  // row of K/16 partials is a whole number of 16-byte pieces).  Loads complete in order: once
+  // the first weight block has arrived the partials are there too, and the wave turns them
+  // into 1/rms while the stream is in flight.
   typedef __attribute__((address_space(3))) void lds_void;
-  const int pchunks = (fu.n_part + 63) >> 6;                          // 64-partial requests per row
-  float* ss_lds = reinterpret_cast<float*>(smem + KS * (NW * 4096));  // [M][pchunks * 64]
+  const int pchunks = (fu.n_part + 255) >> 8;                         // 256-partial requests per row
+  float* ss_lds = reinterpret_cast<float*>(smem + KS * (NW * 4096));  // [M][pchunks * 256]
   if constexpr (NORM && MT == 1) {
-    for (int c = 0; c < 4 * pchunks; ++c) {
-      const int row = wave * 4 + c / pchunks, idx = (c % pchunks) * 64 + lane;
-      if (row < M && idx < fu.n_part)
-        __builtin_amdgcn_global_load_lds((const void*)(fu.ss_in + (size_t)row * fu.n_part + idx),
-                                         (lds_void*)(ss_lds + (row * pchunks + c % pchunks) * 64), 4, 0, 0);
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int row = wave * 4 + r;
+      for (int ch = 0; ch < pchunks; ++ch) {
+        const int idx = ch * 256 + lane * 4;
+        if (row < M && idx < fu.n_part)
+          __builtin_amdgcn_global_load_lds((const void*)(fu.ss_in + (size_t)row * fu.n_part + idx),
+                                           (lds_void*)(ss_lds + (row * pchunks + ch) * 256), 16, 0, 0);
+      }
     }
     __builtin_amdgcn_sched_barrier(0);
   }
@@ -151,7 +157,7 @@ k_gemm_skinny(const bf16* __restrict__ X, const bf16* __restrict__ W, int M, int
             const int row = wave * 4 + (lane >> 4);
             float ss = 0.f;
             if (row < M)
-              for (int idx = lane & 15; idx < fu.n_part; idx += 16) ss += ss_lds[row * (pchunks * 64) + idx];
+              for (int idx = lane & 15; idx < fu.n_part; idx += 16) ss += ss_lds[row * (pchunks * 256) + idx];
             ss = row16_sum(ss);
             if (row < M && (lane & 15) == 0) sm_inv[row] = 1.0f / sqrtf(ss / (float)K + fu.eps);
           }
@@ -221,7 +227,7 @@ void launch_kn(const void* X, const void* W, int M, int N, int K, void* out, flo
   // the K-split partial tiles reuse the scratch areas (KS*NW*MT KB <= KS*NW*4 KB); a NORM
   // kernel for <= 16 rows keeps the rows' partial sums of squares behind them
   const int scratch = KS * NW * 4096;
-  const int ss_bytes = (NORM && MT == 1) ? M * ((fu.n_part + 63) / 64) * 256 : 0;
+  const int ss_bytes = (NORM && MT == 1) ? M * ((fu.n_part + 255) / 256) * 1024 : 0;
   const int smem = scratch + ss_bytes;
   static int attr_bytes = 0;
   if (smem > attr_bytes) {
