@@ -81,12 +81,12 @@ k_gemm_skinny(const bf16* __restrict__ X, const bf16* __restrict__ W, int M, int
 #define LS_LOAD_BLOCK(slot, blk)                                                                 \
   {                                                                                              \
     const size_t kb_ = (size_t)(blk) << 7;                                                       \
-    _Pragma("unroll") for (int t_ = 0; t_ < MT; ++t_)                                            \
-      _Pragma("unroll") for (int k_ = 0; k_ < 4; ++k_)                                           \
-        xr[slot][t_][k_] = *reinterpret_cast<const u32x4*>(X + xoff[t_] + kb_ + k_ * 32);        \
     _Pragma("unroll") for (int s_ = 0; s_ < NW; ++s_)                                            \
       _Pragma("unroll") for (int i_ = 0; i_ < 4; ++i_)                                           \
         wr[slot][s_][i_] = LS_STREAM_LOAD(reinterpret_cast<const u32x4*>(W + woff[s_][i_] + kb_)); \
+    _Pragma("unroll") for (int t_ = 0; t_ < MT; ++t_)                                            \
+      _Pragma("unroll") for (int k_ = 0; k_ < 4; ++k_)                                           \
+        xr[slot][t_][k_] = *reinterpret_cast<const u32x4*>(X + xoff[t_] + kb_ + k_ * 32);        \
   }
 
   // NORM (<= 16 rows): wave w owns rows 4w..4w+3 of the 1/rms computation.  It requests their
@@ -167,8 +167,8 @@ k_gemm_skinny(const bf16* __restrict__ X, const bf16* __restrict__ W, int M, int
   }
 #undef LS_LOAD_BLOCK
 
-  // ---- sum the KS partial tiles in wave order, then the epilogue
-  __syncthreads();  // every wave is done with its scratch; reuse LDS for the partials
+  // ---- sum the KS partial tiles in wave order (through an LDS area of their own: no wait for
+  // the other waves' scratch to fall idle), then the epilogue
   if constexpr (NORM && MT > 1) {
     // more than 16 rows: 1/rms per row straight from the partial sums in global memory
     for (int row = threadIdx.x >> 4; row < M; row += KS * 4) {
@@ -178,7 +178,8 @@ k_gemm_skinny(const bf16* __restrict__ X, const bf16* __restrict__ W, int M, int
       if ((threadIdx.x & 15) == 0) sm_inv[row] = 1.0f / sqrtf(ss / (float)K + fu.eps);
     }
   }
-  float* red = reinterpret_cast<float*>(smem);  // [KS][NW][MT][16 m][16 n]
+  float* red = reinterpret_cast<float*>(smem + KS * (NW * 4096) +
+                                       ((NORM && MT == 1) ? M * pchunks * 1024 : 0));  // [KS][NW][MT][16 m][16 n]
 #pragma unroll
   for (int s = 0; s < NW; ++s)
 #pragma unroll
@@ -221,14 +222,16 @@ template <int MT, int EPI, int KS, bool NORM>
 void launch_kn(const void* X, const void* W, int M, int N, int K, void* out, float* resid, const SkinnyFusion& fu,
                hipStream_t st) {
   constexpr int NW = (EPI == EPI_SWIGLU) ? 2 : 1;
-  // register ring depth in 128-wide K blocks; two blocks measured best for every shape
-  // (a deeper ring costs registers, hence resident wavefronts)
+  // register ring depth in 128-wide K blocks; two blocks measured best for every shape (a
+  // deeper ring costs registers, hence resident wavefronts; also with one 8-wave workgroup
+  // per CU, where registers are free, rings of 3 and 4 blocks and 16 waves ran 0.5-1.6% slower
+  // per decode step: these short kernels are bound by their start and end, not by bytes in flight)
   constexpr int PF = LS_SKINNY_PF ? LS_SKINNY_PF : 2;
-  // the K-split partial tiles reuse the scratch areas (KS*NW*MT KB <= KS*NW*4 KB); a NORM
-  // kernel for <= 16 rows keeps the rows' partial sums of squares behind them
+  // behind the waves' scratch areas: the rows' partial sums of squares (NORM kernel for <= 16
+  // rows), then the K-split partial tiles
   const int scratch = KS * NW * 4096;
   const int ss_bytes = (NORM && MT == 1) ? M * ((fu.n_part + 255) / 256) * 1024 : 0;
-  const int smem = scratch + ss_bytes;
+  const int smem = scratch + ss_bytes + KS * NW * MT * 1024;
   static int attr_bytes = 0;
   if (smem > attr_bytes) {
     (void)hipFuncSetAttribute((const void*)k_gemm_skinny<MT, EPI, KS, PF, NORM>, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
