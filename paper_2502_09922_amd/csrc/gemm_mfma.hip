@@ -3,13 +3,21 @@
 // One 512-thread workgroup (8 wavefronts, 2 x 4) owns a 256 x 256 tile of C and walks K in
 // steps of 64.  Both operands are K-contiguous, so a lane's 16-byte global load is exactly
 // the 8-element K slice an MFMA operand wants.  Tiles go from global memory straight into
-// LDS (global_load_lds_dwordx4: no staging registers, no LDS store instructions), double
-// buffered (128 KB).  One such instruction fills 1 KB = 8 tile rows of 128 bytes; 16-byte
-// chunks are XOR-swizzled by (row/2)&7 -- the lane that fills physical chunk p of row r
-// fetches logical chunk p ^ ((r/2)&7) -- so that the 16 rows a quarter-wave reads for an MFMA
-// operand fall into different banks (LDS has 64 banks here).  v_mfma_f32_32x32x16_bf16: the activation tile is the
-// A operand (rows m), the weight tile the B operand (columns n); in the result a lane holds
-// column n = lane%32 and rows 8*(r/4) + 4*(lane/32) + r%4, r = 0..15.
+// LDS (global_load_lds_dwordx4: no staging registers, no LDS store instructions) through a
+// ring of NS stages: two stages of 64 KB by default.  One such instruction fills 1 KB = 8
+// tile rows of 128 bytes; 16-byte chunks are XOR-swizzled by (row/2)&7 -- the lane that
+// fills physical chunk p of row r fetches logical chunk p ^ ((r/2)&7) -- so that the 16 rows
+// a quarter-wave reads for an MFMA operand fall into different banks (LDS has 64 banks
+// here).  v_mfma_f32_32x32x16_bf16: the activation tile is the A operand (rows m), the
+// weight tile the B operand (columns n); in the result a lane holds column n = lane%32 and
+// rows 8*(r/4) + 4*(lane/32) + r%4, r = 0..15.
+//
+// K-step width and ring depth are compile-time (LS_GEMM_BK 64 or 32, LS_GEMM_NS stages).
+// Measured inside the stage: rings of 3, 4 and 5 stages of 32-wide K steps all run 6% slower
+// than two stages of 64.  The depth of the ring does not matter; the rate at which one CU
+// pulls lines out of L2 does (its vector cache sits stalled on outstanding requests for 44%
+// of the kernel's cycles, L2 hit rate 79%), and 64-byte row pieces cost twice the requests
+// of whole 128-byte lines.
 //
 // Workgroup ids are remapped so that the 32 workgroups resident on one XCD (ids congruent
 // modulo 8 land on the same XCD) work on a 4 x 8 patch of neighbouring tiles and share
@@ -21,16 +29,30 @@ namespace ls {
 
 namespace {
 
-constexpr int BM = 256, BN = 256, BK = 64;
-constexpr int TILE_BYTES = BM * BK * 2;         // 32 KB per operand tile
-constexpr int SMEM_BYTES = 4 * TILE_BYTES;      // A and W, two buffers each
-constexpr int GROUP_M = 4;
-
-#ifndef LS_GEMM_SWZ_SHIFT
-#define LS_GEMM_SWZ_SHIFT 1
+#ifndef LS_GEMM_BK
+#define LS_GEMM_BK 64
 #endif
+#ifndef LS_GEMM_NS
+#define LS_GEMM_NS 2
+#endif
+constexpr int BM = 256, BN = 256, BK = LS_GEMM_BK;
+constexpr int NS = LS_GEMM_NS;                  // ring of NS stages, NS-1 fills in flight
+constexpr int ROWB = BK * 2;                    // bytes per tile row
+constexpr int CH = ROWB / 16;                   // 16-byte chunks per row
+constexpr int RPI = 1024 / ROWB;                // rows per fill instruction
+constexpr int FI = 32 / RPI;                    // fill instructions per operand per wave
+constexpr int KK = BK / 16;                     // MFMA k-steps per stage
+constexpr int SH = (BK == 64) ? 1 : 2;          // swizzle: rows that share a bank group
+constexpr int TILE_BYTES = BM * ROWB;           // per operand tile
+constexpr int STAGE_BYTES = 2 * TILE_BYTES;
+constexpr int SMEM_BYTES = NS * STAGE_BYTES;
+constexpr int GROUP_M = 4;
+// s_waitcnt vmcnt(n), other counters untouched: all fills but those of the last NS-2 stages
+constexpr int VM_KEEP = 2 * FI * (NS - 2);
+constexpr int WAIT_KEEP = 0x0F70 | (VM_KEEP & 15) | ((VM_KEEP >> 4) << 14);
+
 __device__ __forceinline__ int swz(int row, int chunk) {
-  return row * 128 + ((chunk ^ ((row >> LS_GEMM_SWZ_SHIFT) & 7)) << 4);
+  return row * ROWB + ((chunk ^ ((row >> SH) & (CH - 1))) << 4);
 }
 
 template <int EPI>
@@ -57,12 +79,12 @@ k_gemm_mfma(const bf16* __restrict__ A, const bf16* __restrict__ W, int M, int N
 
   // ---- global -> LDS: wave w fills tile rows 32w..32w+31 of both operands, 8 rows per
   // instruction; lane l supplies row 32w + 8i + l/8, physical chunk l%8
-  const bf16* ap[4];
-  const bf16* wp[4];
+  const bf16* ap[FI];
+  const bf16* wp[FI];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int row = wave * 32 + i * 8 + (lane >> 3);
-    const int c = (lane & 7) ^ ((row >> 1) & 7);
+  for (int i = 0; i < FI; ++i) {
+    const int row = wave * 32 + i * RPI + lane / CH;
+    const int c = (lane % CH) ^ ((row >> SH) & (CH - 1));
     const int am = min(m0 + row, M - 1);
     ap[i] = A + (size_t)am * K + c * 8;
     int wrow;
@@ -88,32 +110,32 @@ k_gemm_mfma(const bf16* __restrict__ A, const bf16* __restrict__ W, int M, int N
   const int lr = lane & 31, lh = lane >> 5;
   const int KT = K / BK;
   // LDS byte offsets of this lane's operand reads
-  int a_off[4][4], b_off[4][2];
+  int a_off[KK][4], b_off[KK][2];
 #pragma unroll
-  for (int kk = 0; kk < 4; ++kk) {
+  for (int kk = 0; kk < KK; ++kk) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) a_off[kk][i] = swz(wm * 128 + i * 32 + lr, kk * 2 + lh);
 #pragma unroll
     for (int j = 0; j < 2; ++j) b_off[kk][j] = TILE_BYTES + swz(wn * 64 + j * 32 + lr, kk * 2 + lh);
   }
   typedef __attribute__((address_space(3))) void lds_void;
-  const int fill_off = (wave * 32) * 128;  // this wave's first row inside an operand tile
+  const int fill_off = (wave * 32) * ROWB;  // this wave's first row inside an operand tile
 
 #define LS_FILL_TILE(buf, k0)                                                                          \
-  _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                                      \
+  _Pragma("unroll") for (int i = 0; i < FI; ++i) {                                                     \
     __builtin_amdgcn_global_load_lds((const void*)(ap[i] + (k0)),                                      \
-        (lds_void*)(smem + (buf) * 2 * TILE_BYTES + fill_off + i * 1024), 16, 0, 0);                   \
+        (lds_void*)(smem + (buf) * STAGE_BYTES + fill_off + i * 1024), 16, 0, 0);                      \
     __builtin_amdgcn_global_load_lds((const void*)(wp[i] + (k0)),                                      \
-        (lds_void*)(smem + (buf) * 2 * TILE_BYTES + TILE_BYTES + fill_off + i * 1024), 16, 0, 0);      \
+        (lds_void*)(smem + (buf) * STAGE_BYTES + TILE_BYTES + fill_off + i * 1024), 16, 0, 0);         \
   }
   // operand fragments are double buffered in registers: the LDS reads of k-step kk+1 are
   // issued before the MFMAs of k-step kk, so the matrix pipe does not wait on LDS latency
 #define LS_READ_FRAGS(buf, kk, set)                                                                \
   {                                                                                                \
     _Pragma("unroll") for (int i = 0; i < 4; ++i)                                                  \
-      af[set][i] = *reinterpret_cast<const bf16x8*>(smem + (buf) * 2 * TILE_BYTES + a_off[kk][i]); \
+      af[set][i] = *reinterpret_cast<const bf16x8*>(smem + (buf) * STAGE_BYTES + a_off[kk][i]); \
     _Pragma("unroll") for (int j = 0; j < 2; ++j)                                                  \
-      bfr[set][j] = *reinterpret_cast<const bf16x8*>(smem + (buf) * 2 * TILE_BYTES + b_off[kk][j]); \
+      bfr[set][j] = *reinterpret_cast<const bf16x8*>(smem + (buf) * STAGE_BYTES + b_off[kk][j]); \
   }
 #define LS_MFMA_STEP(set)                                                                          \
   _Pragma("unroll") for (int i = 0; i < 4; ++i)                                                    \
@@ -132,40 +154,44 @@ k_gemm_mfma(const bf16* __restrict__ A, const bf16* __restrict__ W, int M, int N
     bf16x8 af[2][4], bfr[2][2];                                 \
     LS_READ_FRAGS(buf, 0, 0)                                    \
     __builtin_amdgcn_sched_barrier(0);                          \
-    LS_READ_FRAGS(buf, 1, 1)                                    \
-    LS_MFMA_STEP(0)                                             \
-    LS_INTERLEAVE()                                             \
-    __builtin_amdgcn_sched_barrier(0);                          \
-    LS_READ_FRAGS(buf, 2, 0)                                    \
-    LS_MFMA_STEP(1)                                             \
-    LS_INTERLEAVE()                                             \
-    __builtin_amdgcn_sched_barrier(0);                          \
-    LS_READ_FRAGS(buf, 3, 1)                                    \
-    LS_MFMA_STEP(0)                                             \
-    LS_INTERLEAVE()                                             \
-    __builtin_amdgcn_sched_barrier(0);                          \
-    LS_MFMA_STEP(1)                                             \
+    _Pragma("unroll") for (int kk = 0; kk < KK; ++kk) {         \
+      if (kk + 1 < KK) LS_READ_FRAGS(buf, kk + 1, (kk + 1) & 1) \
+      LS_MFMA_STEP(kk & 1)                                      \
+      if (kk + 1 < KK) {                                        \
+        LS_INTERLEAVE()                                         \
+        __builtin_amdgcn_sched_barrier(0);                      \
+      }                                                         \
+    }                                                           \
   }
-  // s_waitcnt vmcnt(0): the fills this wave issued have landed in LDS
-#define LS_WAIT_FILLS() __builtin_amdgcn_s_waitcnt(0x0F70)
+  // the barrier between k-steps: this wave's LDS reads are done (lgkmcnt) and the fills it
+  // issued for the next stage have landed (vmcnt; younger fills stay in flight)
+#define LS_STEP_BARRIER(imm)                 \
+  asm volatile("" ::: "memory");             \
+  __builtin_amdgcn_s_waitcnt(imm);           \
+  __builtin_amdgcn_s_waitcnt(0xC07F);        \
+  __builtin_amdgcn_sched_barrier(0);         \
+  __builtin_amdgcn_s_barrier();              \
+  __builtin_amdgcn_sched_barrier(0);         \
+  asm volatile("" ::: "memory");
 
-  LS_FILL_TILE(0, 0)
-  LS_WAIT_FILLS();
-  __syncthreads();
+#pragma unroll
+  for (int s = 0; s < NS - 1; ++s)
+    if (s < KT) LS_FILL_TILE(s, s * BK)
+  if (KT >= NS - 1) { LS_STEP_BARRIER(WAIT_KEEP) } else { LS_STEP_BARRIER(0x0F70) }
   for (int kt = 0; kt < KT; ++kt) {
-    const int buf = kt & 1;
-    // the other buffer was last read in step kt-1, which every wave has left (barrier)
-    if (kt + 1 < KT) LS_FILL_TILE(buf ^ 1, (kt + 1) * BK)
+    const int buf = kt % NS;
+    // stage (kt-1) % NS was last read in step kt-1, which every wave has left (barrier)
+    const bool more = kt + NS - 1 < KT;
+    if (more) LS_FILL_TILE((kt + NS - 1) % NS, (kt + NS - 1) * BK)
     LS_COMPUTE_TILE(buf)
-    LS_WAIT_FILLS();
-    __syncthreads();
+    if (more) { LS_STEP_BARRIER(WAIT_KEEP) } else { LS_STEP_BARRIER(0x0F70) }
   }
 #undef LS_FILL_TILE
 #undef LS_COMPUTE_TILE
 #undef LS_INTERLEAVE
 #undef LS_READ_FRAGS
 #undef LS_MFMA_STEP
-#undef LS_WAIT_FILLS
+#undef LS_STEP_BARRIER
 
   // ---- epilogue
 #pragma unroll
