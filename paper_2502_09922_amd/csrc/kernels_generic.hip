@@ -68,14 +68,46 @@ __global__ void __launch_bounds__(256) k_decode_prologue(const T* __restrict__ t
   } else {
     src = (const T*)in + (size_t)b * d;
   }
+  // 16-byte accesses when the element is bf16 and the input row is 16-byte aligned (the
+  // workspace rows and the weight slab always are); same arithmetic, same summation order
+  bool vec = false;
+  if constexpr (sizeof(T) == 2) vec = ((reinterpret_cast<uintptr_t>(src) | reinterpret_cast<uintptr_t>(gamma)) & 15) == 0;
   for (int tile = threadIdx.x; tile < (d >> 4); tile += 256) {
     float ss = 0.f;
+    const size_t o = (size_t)b * d + tile * 16;
+    if constexpr (sizeof(T) == 2) {
+      if (vec) {
+        bf16x8 raw[2], g[2], y[2];
+        raw[0] = *reinterpret_cast<const bf16x8*>(src + tile * 16);
+        raw[1] = *reinterpret_cast<const bf16x8*>(src + tile * 16 + 8);
+        if (gamma) {
+          g[0] = *reinterpret_cast<const bf16x8*>(gamma + tile * 16);
+          g[1] = *reinterpret_cast<const bf16x8*>(gamma + tile * 16 + 8);
+        }
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+          f32x4 lo, hi;
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            const float v = (float)raw[h][e];
+            if (e < 4) lo[e] = v; else hi[e - 4] = v;
+            y[h][e] = gamma ? (bf16)(v * (float)g[h][e]) : raw[h][e];
+            ss += v * v;
+          }
+          *reinterpret_cast<f32x4*>(x + o + h * 8) = lo;
+          *reinterpret_cast<f32x4*>(x + o + h * 8 + 4) = hi;
+          *reinterpret_cast<bf16x8*>(xb + o + h * 8) = y[h];
+        }
+        ss_part[(size_t)b * (d >> 4) + tile] = ss;
+        continue;
+      }
+    }
 #pragma unroll
     for (int e = 0; e < 16; ++e) {
       const T raw = src[tile * 16 + e];
       const float v = to_f(raw);
-      x[(size_t)b * d + tile * 16 + e] = v;
-      xb[(size_t)b * d + tile * 16 + e] = gamma ? from_f<T>(v * to_f(gamma[tile * 16 + e])) : raw;
+      x[o + e] = v;
+      xb[o + e] = gamma ? from_f<T>(v * to_f(gamma[tile * 16 + e])) : raw;
       ss += v * v;
     }
     ss_part[(size_t)b * (d >> 4) + tile] = ss;
