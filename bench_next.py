@@ -6,8 +6,10 @@
   --mode kvrecompute  mode switch (Section 4.4): rebuilding a stage's KV cache by one prompt
                       pass over prompt + generated tokens, against copying the cache
   --mode blocks       block granularity on the host-to-device path (Section 7.6): the model
-                      streamed as blocks of 1, 2, 4, 8 layers and as one block, and one copy
-                      per tensor instead of one per packed block (tensor packing, Section 5)
+                      streamed as blocks of 1, 2, 4, 8 layers and as one block; one copy per
+                      tensor and two per layer instead of one per packed block (tensor packing,
+                      Section 5); a fresh device allocation per block instead of the slab
+                      allocated up front (GPU memory pre-allocation, Section 5)
 
 Each mode prints ONE JSON line.  Weights are seeded N(0, 0.02) as in bench.py.
 """
@@ -199,6 +201,36 @@ def blocks_mode(args):
                     slab[base + o: base + o + n].copy_(big[base + o: base + o + n], non_blocking=True)
     per_tensor()
     t_tensor = wall_ms(torch, per_tensor, args.steps)
+    # half-layer blocks: the attention tensors and the FFN tensors of a layer as two copies
+    half = spans[3][0]  # offset of the FFN norm gain = end of the attention half
+    def half_layer():
+        with torch.cuda.stream(copy):
+            for l in range(lo, hi):
+                base = (l - lo) * per
+                slab[base: base + half].copy_(big[base: base + half], non_blocking=True)
+                slab[base + half: base + per].copy_(big[base + half: base + per], non_blocking=True)
+    half_layer()
+    t_half = wall_ms(torch, half_layer, args.steps)
+    # allocate on arrival: a fresh device allocation per block (hipMalloc, then the copy, freed
+    # afterwards) instead of the slab allocated once up front (Section 5, GPU memory pre-allocation)
+    hip = B.C.CDLL("libamdhip64.so")
+    hip.hipMalloc.argtypes = [B.C.POINTER(B.C.c_void_p), B.C.c_size_t]
+    hip.hipFree.argtypes = [B.C.c_void_p]
+    hip.hipMemcpyAsync.argtypes = [B.C.c_void_p, B.C.c_void_p, B.C.c_size_t, B.C.c_int, B.C.c_void_p]
+    def alloc_on_arrival():
+        ptrs = []
+        for l in range(lo, hi):
+            ptr = B.C.c_void_p()
+            assert hip.hipMalloc(B.C.byref(ptr), per) == 0
+            assert hip.hipMemcpyAsync(ptr, big.data_ptr() + (l - lo) * per, per, 1, copy.cuda_stream) == 0
+            ptrs.append(ptr)
+        copy.synchronize()
+        return ptrs
+    def alloc_run():
+        for ptr in alloc_on_arrival():
+            assert hip.hipFree(ptr) == 0
+    alloc_run()
+    t_alloc = wall_ms(torch, alloc_run, args.steps)
     best = min(rows, key=lambda r: r["ttft_streamed_ms"])
     out = {
         "metric": "time-to-first-token by block granularity, model streamed from pinned host memory (1 GPU)",
@@ -209,7 +241,10 @@ def blocks_mode(args):
                    "model_bytes": per * (hi - lo)},
         "block_granularity": {"prefill_alone_ms": t_compute, "sweep": rows,
                               "copy_one_per_tensor_ms": t_tensor,
-                              "copy_one_per_packed_block_ms": rows[0]["copy_alone_ms"]},
+                              "copy_two_per_layer_ms": t_half,
+                              "copy_one_per_packed_block_ms": rows[0]["copy_alone_ms"],
+                              "copy_into_fresh_allocation_per_block_ms": t_alloc,
+                              "note": "the fresh-allocation figure includes the 32 hipMalloc and hipFree calls"},
     }
     print(json.dumps(out))
     st.close()
