@@ -96,9 +96,10 @@ def test_one_layer_slices_at_real_dimensions(name, lo, hi, lengths, steps):
     gpu.close()
 
 
-@pytest.mark.parametrize("batch", [20, 40, 64])
+@pytest.mark.parametrize("batch", [13, 16, 17, 20, 40, 64])
 def test_decode_with_many_sequences(batch):
-    """Decode batches of 17..64 rows take the wider weight-streaming kernel variants."""
+    """Decode batches of 17..64 rows take the wider weight-streaming kernel variants; 13 and
+    16 rows are the upper end of the narrow one (every wavefront owns rows of the folded norm)."""
     shape, seed, steps = synth.StageShape("bf16", 2, 512, 8, 2, 64, 1408, 0), 31, 3
     lengths = [int(n) for n in synth.ragged_lengths(seed, batch, 1, 12)]
     S, T = max(lengths), sum(lengths)
