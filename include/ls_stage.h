@@ -349,6 +349,20 @@ ls_status ls_plan_pipelines(const int32_t* sizes, int k, int32_t* group_out, int
  * n_blocks + ceil(log2 n_nodes) - 1 (Section 4.2); LS_ERR_INVALID_ARG (negative) on bad input. */
 int ls_plan_multicast_steps(int n_blocks, int n_nodes);
 
+/*
+ * One schedule of that multicast that takes exactly n_blocks + log2(n_nodes) - 1 steps, for
+ * n_nodes a power of two >= 2 and node 0 holding all blocks at the start (Section 4.2 names
+ * the technique and its step count; the schedule is this library's construction).  In step
+ * s node u exchanges with node u XOR 2^(s mod log2 n_nodes): dest[s * n_nodes + u] is that
+ * partner and block[s * n_nodes + u] the block u sends it, or both -1 if u sends nothing in
+ * step s.  A node sends at most one block and receives at most one per step, never a block
+ * the receiver already holds.  dest and block hold capacity_steps * n_nodes entries
+ * (LS_ERR_OOM if more steps are needed); *n_steps receives the number of steps written.
+ * Host arrays; LS_ERR_INVALID_ARG on bad input.
+ */
+ls_status ls_plan_multicast_schedule(int n_blocks, int n_nodes, int32_t* dest, int32_t* block, int capacity_steps,
+                                     int* n_steps);
+
 /* 1 if every duration ls_stage_probe_times would return now is a kernel's own start-to-stop
  * time, 0 if some are spans between recorded events (or nothing was probed). */
 int ls_stage_probe_is_kernel_exact(const ls_stage* stage);

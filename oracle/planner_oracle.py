@@ -5,6 +5,10 @@ product never does).  Plain Python, integers only.
   * sub-group sizes for k -> N scaling: Section 4.2, "Multicast and sub-groups".
   * execution pipeline generation: Section 4.3, Algorithm 2.
   * number of multicast steps of the binomial pipeline: Section 4.2 (b + ceil(log2 N) - 1).
+  * a step-by-step schedule of that multicast for N = 2^n nodes.  The paper only cites the
+    technique and states its step count; the schedule here is a construction of this build
+    (exchange partners walk the hypercube dimensions, every node forwards its newest useful
+    block) that meets the stated count.
 
 Reading taken where the text is garbled: the sentence on sub-group sizes gives "floor(N/k) or
 N%k"; a remainder is not a size, so the N nodes are dealt out as evenly as possible: the
@@ -60,3 +64,33 @@ def multicast_steps(b, n_nodes):
     while (1 << log) < n_nodes:
         log += 1
     return b + log - 1
+
+
+def multicast_schedule(b, n_nodes):
+    """1 -> n_nodes multicast of b blocks from node 0, n_nodes a power of two.  Returns a list
+    of steps; step s is a dict {sender: (receiver, block)}.  In step s every node u is paired
+    with u XOR 2^(s mod n); node 0 offers block s while there are new ones, every other node
+    (and node 0 afterwards) the highest-numbered block it holds that its partner lacks.  All
+    transfers of a step happen at once."""
+    n = n_nodes.bit_length() - 1
+    assert n_nodes == 1 << n and b >= 1
+    have = [set() for _ in range(n_nodes)]
+    have[0] = set(range(b))
+    steps = []
+    while any(len(h) < b for h in have):
+        s = len(steps)
+        bit = 1 << (s % n)
+        sends = {}
+        for u in range(n_nodes):
+            v = u ^ bit
+            useful = [k for k in have[u] if k not in have[v]]
+            if not useful:
+                continue
+            k = max(useful)
+            if u == 0 and min(s, b - 1) in useful:
+                k = min(s, b - 1)
+            sends[u] = (v, k)
+        for u, (v, k) in sends.items():
+            have[v].add(k)
+        steps.append(sends)
+    return steps

@@ -92,6 +92,8 @@ _SIGS = {
     "ls_plan_pipelines": (C.c_int, [C.POINTER(C.c_int32), C.c_int, C.POINTER(C.c_int32), C.POINTER(C.c_int32),
                                     C.POINTER(C.c_int32), C.c_int, C.POINTER(C.c_int)]),
     "ls_plan_multicast_steps": (C.c_int, [C.c_int, C.c_int]),
+    "ls_plan_multicast_schedule": (C.c_int, [C.c_int, C.c_int, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.c_int,
+                                             C.POINTER(C.c_int)]),
     "ls_last_error": (C.c_char_p, []),
 }
 for _name, (_res, _args) in _SIGS.items():

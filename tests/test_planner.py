@@ -96,7 +96,122 @@ def test_multicast_step_count_closed_form():
         assert po.multicast_steps(8, n) == 8 + math.ceil(math.log2(n)) - 1
 
 
+def replay(b_, n_nodes, steps):
+    """Plays a multicast schedule; checks that it is executable and returns who holds what."""
+    n = n_nodes.bit_length() - 1
+    have = [set() for _ in range(n_nodes)]
+    have[0] = set(range(b_))
+    for s, sends in enumerate(steps):
+        got = []
+        for u, (v, k) in sends.items():
+            assert v == u ^ (1 << (s % n)), "partners walk the hypercube dimensions"
+            assert k in have[u], "a node can only send what it holds at the start of the step"
+            assert k not in have[v], "no block is sent to a node that already holds it"
+            got.append((v, k))
+        assert len({v for v, _ in got}) == len(got), "at most one block received per step"
+        for v, k in got:
+            have[v].add(k)
+    return have
+
+
+@pytest.mark.parametrize("n_nodes", [2, 4, 8, 16, 32])
+def test_multicast_schedule_meets_the_step_count_of_section_4_2(n_nodes):
+    """Section 4.2: a binomial-pipeline multicast of b blocks to N nodes takes b + log2 N - 1
+    steps.  The oracle's schedule must be executable (senders hold what they send, one block
+    in and one out per node and step), complete, free of redundant transfers, and exactly that
+    long -- which is also the fewest steps possible: the last block cannot leave node 0 before
+    step b - 1 and a block needs log2 N more steps to reach N nodes by doubling."""
+    n = n_nodes.bit_length() - 1
+    for nb in list(range(1, 12)) + [32, 34]:
+        steps = po.multicast_schedule(nb, n_nodes)
+        assert len(steps) == nb + n - 1 == po.multicast_steps(nb, n_nodes)
+        have = replay(nb, n_nodes, steps)
+        assert all(h == set(range(nb)) for h in have)
+        assert sum(len(x) for x in steps) == nb * (n_nodes - 1)
+        for s in range(nb):  # the source injects block s at step s
+            assert steps[s][0][1] == s
+
+
+def test_multicast_schedule_special_cases():
+    # one block: the classic binomial tree, holders double every step
+    steps = po.multicast_schedule(1, 16)
+    holders = {0}
+    for s, sends in enumerate(steps):
+        assert set(sends) == holders
+        holders |= {v for v, _ in sends.values()}
+        assert len(holders) == 2 ** (s + 1)
+    # two nodes: the source sends block s at step s, nothing else happens
+    assert po.multicast_schedule(5, 2) == [{0: (1, s)} for s in range(5)]
+
+
+def test_no_schedule_is_shorter_brute_force():
+    """Exhaustive search over ALL schedules (any node may send any block it holds to any node,
+    one block out and one in per node and step) for 4 nodes: none completes in fewer than
+    b + 1 steps, so the oracle's schedule is optimal there."""
+    def fewest(nb, n_nodes):
+        start = tuple([frozenset(range(nb))] + [frozenset()] * (n_nodes - 1))
+        full = frozenset(range(nb))
+        frontier, seen, steps = {start}, {start}, 0
+        while True:
+            if any(all(h == full for h in st) for st in frontier):
+                return steps
+            nxt = set()
+            for st in frontier:
+                options = []
+                for u in range(n_nodes):
+                    opts = [None] + [(v, k) for v in range(n_nodes) if v != u for k in st[u] - st[v]]
+                    options.append(opts)
+                for choice in itertools.product(*options):
+                    dests = [c[0] for c in choice if c]
+                    if len(set(dests)) != len(dests):
+                        continue
+                    new = [set(h) for h in st]
+                    for c in choice:
+                        if c:
+                            new[c[0]].add(c[1])
+                    t = tuple(frozenset(h) for h in new)
+                    if t not in seen:
+                        seen.add(t)
+                        nxt.add(t)
+            frontier, steps = nxt, steps + 1
+    for nb in (1, 2, 3):
+        assert fewest(nb, 4) == nb + 1 == len(po.multicast_schedule(nb, 4))
+    assert fewest(2, 2) == 2
+
+
 # ---- the library against the oracle ------------------------------------------------------------
+def c_multicast(nb, n_nodes):
+    cap = nb + 8
+    dest, blk = (C.c_int32 * (cap * n_nodes))(), (C.c_int32 * (cap * n_nodes))()
+    n = C.c_int()
+    assert b.ls_plan_multicast_schedule(nb, n_nodes, dest, blk, cap, C.byref(n)) == 0
+    out = []
+    for s in range(n.value):
+        step = {}
+        for u in range(n_nodes):
+            d, k = dest[s * n_nodes + u], blk[s * n_nodes + u]
+            assert (d < 0) == (k < 0)
+            if d >= 0:
+                step[u] = (d, k)
+        out.append(step)
+    return out
+
+
+def test_library_multicast_schedule_matches_the_oracle_bit_for_bit():
+    for n_nodes in (2, 4, 8, 16, 64):
+        for nb in list(range(1, 20)) + [63, 64, 65, 130]:
+            assert c_multicast(nb, n_nodes) == po.multicast_schedule(nb, n_nodes), (nb, n_nodes)
+
+
+def test_library_multicast_schedule_rejects_bad_arguments():
+    arr = (C.c_int32 * 64)()
+    n = C.c_int()
+    for nb, nn in ((0, 4), (4, 1), (4, 3), (4, 6), (4, 0), (-1, 4)):
+        assert b.ls_plan_multicast_schedule(nb, nn, arr, arr, 16, C.byref(n)) == b.LS_ERR_INVALID_ARG
+    assert b.ls_plan_multicast_schedule(4, 4, None, arr, 16, C.byref(n)) == b.LS_ERR_INVALID_ARG
+    assert b.ls_plan_multicast_schedule(4, 4, arr, arr, 4, C.byref(n)) == b.LS_ERR_OOM  # 5 steps needed
+
+
 def c_kway(nb, k, g):
     arr = (C.c_int32 * max(nb, 1))()
     assert b.ls_plan_kway_order(nb, k, g, arr) == 0
