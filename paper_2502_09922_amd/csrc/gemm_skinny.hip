@@ -58,6 +58,32 @@ k_gemm_skinny(const bf16* __restrict__ X, const bf16* __restrict__ W, int M, int
       const int row = 4 * i + lg;
       woff[s][i] = (size_t)(s * N + n0 + row) * K + (size_t)((lr ^ row) << 3);
     }
+  u32x4 wr[PF][NW][4];
+  // weights are read exactly once per launch: non-temporal loads keep them from displacing
+  // the activations in the caches and stream measurably faster out of HBM
+#ifndef LS_STREAM_LOAD
+#define LS_STREAM_LOAD(p) __builtin_nontemporal_load(p)
+#endif
+#define LS_LOAD_W(slot, blk)                                                                     \
+  {                                                                                              \
+    const size_t kb_ = (size_t)(blk) << 7;                                                       \
+    _Pragma("unroll") for (int s_ = 0; s_ < NW; ++s_)                                            \
+      _Pragma("unroll") for (int i_ = 0; i_ < 4; ++i_)                                           \
+        wr[slot][s_][i_] = LS_STREAM_LOAD(reinterpret_cast<const u32x4*>(W + woff[s_][i_] + kb_)); \
+  }
+#define LS_LOAD_X(slot, blk)                                                                     \
+  {                                                                                              \
+    const size_t kb_ = (size_t)(blk) << 7;                                                       \
+    _Pragma("unroll") for (int t_ = 0; t_ < MT; ++t_)                                            \
+      _Pragma("unroll") for (int k_ = 0; k_ < 4; ++k_)                                           \
+        xr[slot][t_][k_] = *reinterpret_cast<const u32x4*>(X + xoff[t_] + kb_ + k_ * 32);        \
+  }
+#define LS_LOAD_BLOCK(slot, blk) { LS_LOAD_W(slot, blk) LS_LOAD_X(slot, blk) }
+  // the first weight block is requested before any other address is worked out: the sooner
+  // the stream starts, the shorter the kernel (every wavefront has at least one block)
+  LS_LOAD_W(0, b0)
+  __builtin_amdgcn_sched_barrier(0);
+
   size_t xoff[MT];
 #pragma unroll
   for (int t = 0; t < MT; ++t) xoff[t] = (size_t)min(lr + 16 * t, M - 1) * K + (size_t)(lg << 3);
@@ -65,7 +91,6 @@ k_gemm_skinny(const bf16* __restrict__ X, const bf16* __restrict__ W, int M, int
 #pragma unroll
   for (int kk = 0; kk < 4; ++kk) a_off[kk] = lr * 256 + (((kk * 4 + lg) ^ lr) << 4);
 
-  u32x4 wr[PF][NW][4];
   u32x4 xr[PF][MT][4];
   f32x4 acc[NW][MT];
 #pragma unroll
@@ -73,27 +98,11 @@ k_gemm_skinny(const bf16* __restrict__ X, const bf16* __restrict__ W, int M, int
 #pragma unroll
     for (int t = 0; t < MT; ++t) acc[s][t] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  // weights are read exactly once per launch: non-temporal loads keep them from displacing
-  // the activations in the caches and stream measurably faster out of HBM
-#ifndef LS_STREAM_LOAD
-#define LS_STREAM_LOAD(p) __builtin_nontemporal_load(p)
-#endif
-#define LS_LOAD_BLOCK(slot, blk)                                                                 \
-  {                                                                                              \
-    const size_t kb_ = (size_t)(blk) << 7;                                                       \
-    _Pragma("unroll") for (int s_ = 0; s_ < NW; ++s_)                                            \
-      _Pragma("unroll") for (int i_ = 0; i_ < 4; ++i_)                                           \
-        wr[slot][s_][i_] = LS_STREAM_LOAD(reinterpret_cast<const u32x4*>(W + woff[s_][i_] + kb_)); \
-    _Pragma("unroll") for (int t_ = 0; t_ < MT; ++t_)                                            \
-      _Pragma("unroll") for (int k_ = 0; k_ < 4; ++k_)                                           \
-        xr[slot][t_][k_] = *reinterpret_cast<const u32x4*>(X + xoff[t_] + kb_ + k_ * 32);        \
-  }
-
   // NORM (<= 16 rows): wave w owns rows 4w..4w+3 of the 1/rms computation.  It requests their
-  // partial sums of squares straight into LDS (no registers held) BEFORE the weight ring, 16
+  // partial sums of squares straight into LDS (no registers held) BEFORE its activation loads, 16
   // bytes per lane, so one request covers 256 partials of a row (K is a multiple of 128, so a
   // row of K/16 partials is a whole number of 16-byte pieces).  Loads complete in order: once
-  // the first weight block has arrived the partials are there too, and the wave turns them
+  // the first block (weights and activations) has arrived the partials are there too, and the wave turns them
   // into 1/rms while the stream is in flight.
   typedef __attribute__((address_space(3))) void lds_void;
   const int pchunks = (fu.n_part + 255) >> 8;                         // 256-partial requests per row
@@ -111,8 +120,9 @@ k_gemm_skinny(const bf16* __restrict__ X, const bf16* __restrict__ W, int M, int
     }
     __builtin_amdgcn_sched_barrier(0);
   }
+  LS_LOAD_X(0, b0)
 #pragma unroll
-  for (int p = 0; p < PF; ++p)
+  for (int p = 1; p < PF; ++p)
     if (p < nb) LS_LOAD_BLOCK(p, b0 + p)
 
   // residual epilogue: the element this thread will update is known now; fetch it while the
@@ -166,6 +176,8 @@ k_gemm_skinny(const bf16* __restrict__ X, const bf16* __restrict__ W, int M, int
     }
   }
 #undef LS_LOAD_BLOCK
+#undef LS_LOAD_W
+#undef LS_LOAD_X
 
   // ---- sum the KS partial tiles in wave order (through an LDS area of their own: no wait for
   // the other waves' scratch to fall idle), then the epilogue
