@@ -63,7 +63,7 @@ k_attn_prefill(const bf16* __restrict__ qkv, int qkv_stride, const bf16* __restr
 #pragma unroll
     for (int i = 0; i < 16; ++i) o[dt][i] = 0.f;
   float m_run = -INFINITY, l_run = 0.f;  // l_run: this lane's half of the row sum
-  const float c = 1.4426950408889634f / sqrtf((float)HD);  // scores are kept in log2 units
+  const float c = 1.4426950408889634f / sqrtf((float)HD);  // score -> exponent of 2
 
   const int kv_end = min(q0 + BQ, len);          // keys this tile can see
   const int ntk = (kv_end + BKV - 1) / BKV;
@@ -131,31 +131,39 @@ k_attn_prefill(const bf16* __restrict__ qkv, int qkv_stride, const bf16* __restr
         s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ksn], s[kt], 0, 0, 0);
       }
     }
-    // ---- scale, causal mask, online softmax (all for this lane's query row)
-    const bool diag = (t0 + BKV - 1) > (q0 + wave * 32);  // some key of the tile may be masked
+    // ---- causal mask, online softmax (all for this lane's query row).  Scores stay unscaled:
+    // the running maximum is kept in score units and the scale (with the change to base 2)
+    // is folded into the exponential's argument, p = 2^(c s - c m).
+    // `diag` is the same for the whole wavefront: tiles left of the diagonal skip the mask.
+    const bool diag = __builtin_amdgcn_readfirstlane((int)((t0 + BKV - 1) > (q0 + wave * 32))) != 0;
     float mx = -INFINITY;
+    if (diag) {
 #pragma unroll
-    for (int kt = 0; kt < 2; ++kt)
+      for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        float v = s[kt][i] * c;
-        if (diag) {
+        for (int i = 0; i < 16; ++i) {
           const int key = t0 + kt * 32 + 8 * (i >> 2) + 4 * lh + (i & 3);
-          v = key > qpos ? -INFINITY : v;
+          const float v = key > qpos ? -INFINITY : s[kt][i];
+          s[kt][i] = v;
+          mx = fmaxf(mx, v);
         }
-        s[kt][i] = v;
-        mx = fmaxf(mx, v);
-      }
+    } else {
+#pragma unroll
+      for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[kt][i]);
+    }
     mx = fmaxf(mx, __shfl_xor(mx, 32));
     const float m_new = fmaxf(m_run, mx);  // finite from the first tile on: key 0 is visible
-    const float corr = __builtin_amdgcn_exp2f(m_run - m_new);
+    const float corr = __builtin_amdgcn_exp2f((m_run - m_new) * c);
+    const float mc = m_new * c;
     float psum = 0.f;
     bf16x8 pf[4];
 #pragma unroll
     for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
-        const float p = __builtin_amdgcn_exp2f(s[kt][i] - m_new);
+        const float p = __builtin_amdgcn_exp2f(fmaf(s[kt][i], c, -mc));
         psum += p;
         pf[kt * 2 + (i >> 3)][i & 7] = (bf16)p;
       }
