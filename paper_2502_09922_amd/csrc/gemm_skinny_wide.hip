@@ -29,7 +29,10 @@ __global__ void __launch_bounds__(WAVES * 64)
 k_gemm_wide(const bf16* __restrict__ X, const bf16* __restrict__ W, int M, int N, int K,
             float* __restrict__ part, int blocks_per_split) {
   constexpr int NW = GLU ? 2 : 1;
-  constexpr int PF = 2;
+#ifndef LS_WIDE_PF
+#define LS_WIDE_PF 2
+#endif
+  constexpr int PF = LS_WIDE_PF;
   constexpr int XS_BYTES = MT * 16 * 256;  // one staged X block
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   unsigned char* xs = smem;                                   // [2][MT*16 rows][256 B]
@@ -112,13 +115,15 @@ k_gemm_wide(const bf16* __restrict__ X, const bf16* __restrict__ W, int M, int N
 
   if (nb > 0) {
     LS_LOAD_X(b0)
-    LS_LOAD_W(0, b0)
-    if (nb > 1) LS_LOAD_W(1, b0 + 1)
+#pragma unroll
+    for (int p = 0; p < PF; ++p)
+      if (p < nb) LS_LOAD_W(p, b0 + p)
     LS_STORE_X(0)
     __syncthreads();
-    for (int b = 0; b < nb; b += 2) {  // nb is the same for every wavefront of the workgroup
-      LS_STEP(0, b)
-      if (b + 1 < nb) LS_STEP(1, b + 1)
+    for (int b = 0; b < nb; b += PF) {  // nb is the same for every wavefront of the workgroup
+#pragma unroll
+      for (int sl = 0; sl < PF; ++sl)
+        if (b + sl < nb) LS_STEP(sl, b + sl)
     }
   }
 #undef LS_LOAD_W
