@@ -143,31 +143,36 @@ k_gemm_wide(const bf16* __restrict__ X, const bf16* __restrict__ W, int M, int N
 }
 
 // Adds the K-split partials in split order, then the epilogue.  One 256-thread workgroup per
-// (row, 256 columns).
+// (row, 1024 columns); a thread owns four consecutive columns (16-byte accesses).
 template <int EPI, bool NORM>
 __global__ void __launch_bounds__(256)
 k_wide_finish(const float* __restrict__ part, int splits, int M, int N, int K, void* __restrict__ outv,
               float* __restrict__ resid, SkinnyFusion fu) {
   constexpr int NW = (EPI == EPI_SWIGLU) ? 2 : 1;
   __shared__ float wsum[4];
-  const int m = blockIdx.y, n = blockIdx.x * 256 + threadIdx.x;
+  const int m = blockIdx.y, n = (blockIdx.x * 256 + threadIdx.x) * 4;
   // everything this thread needs from global memory is requested before the row's 1/rms is
   // worked out, so the two latencies overlap
-  const bool live = n < N;  // N % 16 == 0: 16-lane groups are live or not together
+  const bool live = n < N;  // N % 64 == 0: groups of four lanes (16 columns) are live or not together
   const size_t o = (size_t)m * N + (live ? n : 0);
-  float v[NW];
+  f32x4 v[NW];
 #pragma unroll
   for (int s = 0; s < NW; ++s) {
-    float sum = 0.f;
+    f32x4 sum = {0.f, 0.f, 0.f, 0.f};
     if (live)
-      for (int sp = 0; sp < splits; ++sp) sum += part[(((size_t)sp * NW + s) * M + m) * N + n];
+      for (int sp = 0; sp < splits; ++sp)
+        sum += *reinterpret_cast<const f32x4*>(part + (((size_t)sp * NW + s) * M + m) * N + n);
     v[s] = sum;
   }
-  float x_old = 0.f, gain = 1.f;
+  f32x4 x_old = {0.f, 0.f, 0.f, 0.f}, gain = {1.f, 1.f, 1.f, 1.f};
   if constexpr (EPI == EPI_RESID) {
     if (live) {
-      x_old = resid[o];
-      if (fu.gamma_out) gain = (float)fu.gamma_out[n];
+      x_old = *reinterpret_cast<const f32x4*>(resid + o);
+      if (fu.gamma_out) {
+        const bf16x4 g = *reinterpret_cast<const bf16x4*>(fu.gamma_out + n);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) gain[e] = (float)g[e];
+      }
     }
   }
   float inv = 1.f;
@@ -182,18 +187,34 @@ k_wide_finish(const float* __restrict__ part, int splits, int M, int N, int K, v
   if (!live) return;
 #pragma unroll
   for (int s = 0; s < NW; ++s) v[s] *= inv;
-  if constexpr (EPI == EPI_STORE) ((bf16*)outv)[o] = (bf16)v[0];
-  else if constexpr (EPI == EPI_RESID) {
-    const float xn = x_old + v[0];
-    resid[o] = xn;
+  if constexpr (EPI == EPI_STORE) {
+    bf16x4 y;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) y[e] = (bf16)v[0][e];
+    *reinterpret_cast<bf16x4*>((bf16*)outv + o) = y;
+  } else if constexpr (EPI == EPI_RESID) {
+    const f32x4 xn = x_old + v[0];
+    *reinterpret_cast<f32x4*>(resid + o) = xn;
     if (fu.xb_out) {
-      fu.xb_out[o] = (bf16)(xn * gain);
-      const float ss = row16_sum(xn * xn);
-      if ((n & 15) == 0) fu.ss_out[(size_t)m * (N >> 4) + (n >> 4)] = ss;
+      bf16x4 y;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) y[e] = (bf16)(xn[e] * gain[e]);
+      *reinterpret_cast<bf16x4*>(fu.xb_out + o) = y;
+      // sum of squares of the 16-column tile: this thread's four columns in order, then the
+      // four threads of the tile by a fixed exchange
+      float ss = ((xn[0] * xn[0] + xn[1] * xn[1]) + xn[2] * xn[2]) + xn[3] * xn[3];
+      ss += __shfl_xor(ss, 1);
+      ss += __shfl_xor(ss, 2);
+      if ((threadIdx.x & 3) == 0) fu.ss_out[(size_t)m * (N >> 4) + (n >> 4)] = ss;
     }
+  } else if constexpr (EPI == EPI_SWIGLU) {
+    bf16x4 y;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) y[e] = (bf16)(silu_f(v[0][e]) * v[NW - 1][e]);
+    *reinterpret_cast<bf16x4*>((bf16*)outv + o) = y;
+  } else {
+    *reinterpret_cast<f32x4*>((float*)outv + o) = v[0];
   }
-  else if constexpr (EPI == EPI_SWIGLU) ((bf16*)outv)[o] = (bf16)(silu_f(v[0]) * v[NW - 1]);
-  else ((float*)outv)[o] = v[0];
 }
 
 template <int MT, bool GLU>
@@ -218,7 +239,7 @@ void launch_mt(const void* X, const void* W, int M, int N, int K, float* part, i
 template <int EPI>
 void launch_finish(const float* part, int splits, int M, int N, int K, void* out, float* resid,
                    const SkinnyFusion& fu, hipStream_t st) {
-  dim3 grid((N + 255) / 256, M);
+  dim3 grid((N + 1023) / 1024, M);
   if (fu.ss_in) k_wide_finish<EPI, true><<<grid, 256, 0, st>>>(part, splits, M, N, K, out, resid, fu);
   else k_wide_finish<EPI, false><<<grid, 256, 0, st>>>(part, splits, M, N, K, out, resid, fu);
 }
