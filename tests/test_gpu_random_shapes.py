@@ -44,3 +44,31 @@ def test_seeded_sweep_of_shapes_batches_and_ragged_lengths(sweep_seed):
             row_err = np.linalg.norm(got - want, axis=1) / np.linalg.norm(want, axis=1)
             assert row_err.max() <= 3 * TOL, (what, t, int(row_err.argmax()))
         gpu.close()
+
+
+def whole_model_cases(seed, n):
+    rng = np.random.default_rng(seed)
+    for _ in range(n):
+        dtype = str(rng.choice(["bf16", "bf16", "f32"]))
+        hd = int(rng.choice([64, 128]))
+        hkv = int(rng.choice([1, 2]))
+        group = int(rng.choice([1, 2, 4]))
+        d = int(rng.choice([256, 512, 768]))
+        ffn = int(rng.choice([256, 688, 1408]))
+        vocab = int(rng.choice([512, 1000, 4096]))
+        batch = int(rng.choice([1, 3, 8, 17, 20]))
+        lengths = [int(x) for x in rng.integers(1, 40, size=batch)]
+        yield synth.StageShape(dtype, 2, d, hkv * group, hkv, hd, ffn, vocab), lengths, int(rng.integers(0, 10000))
+
+
+def test_seeded_sweep_of_whole_models_with_embedding_and_head():
+    """Embedding gather, layers, final norm, LM head and greedy argmax as one stage, fp32 and
+    bf16: logits against the oracle, greedy tokens teacher-forced and tie-adjusted."""
+    from test_gpu_parity import TOL as TOLS, run_full_model
+
+    for shape, lengths, seed in whole_model_cases(5, 16):
+        errs, agree = run_full_model(shape, seed, lengths, 2)
+        assert max(errs) <= TOLS[shape.dtype], (shape, lengths, seed, errs)
+        adj = sum(a[1] for a in agree)
+        n = sum(a[2] for a in agree)
+        assert adj >= 0.99 * n, (shape, lengths, seed, agree)
