@@ -193,6 +193,14 @@ def recorded_traffic(workload):
         return None
 
 
+def device_info(torch):
+    """What the run was measured on (name, compute units, memory; the library the timed calls ran in)."""
+    p = torch.cuda.get_device_properties(0)
+    import paper_2502_09922_amd.binding as B
+    return {"name": p.name, "arch": getattr(p, "gcnArchName", ""), "compute_units": p.multi_processor_count,
+            "hbm_bytes": p.total_memory, "library": os.path.relpath(B.LIB_PATH, ROOT)}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -339,6 +347,7 @@ def main():
         "vs_baseline": None,
         "dtype": "f32" if shape.dtype == "f32" else "bf16",
         "data": "synthetic",
+        "device": device_info(torch),
         "config": {"workload": args.workload, "layers": [lo, hi], "batch": batch,
                    "prompt": prompt if isinstance(prompt, int) else {"ragged": list(prompt), "total_tokens": T},
                    "decode_steps": dsteps, "weights_gen_s": round(t_gen, 1)},
