@@ -367,6 +367,22 @@ ls_status ls_plan_multicast_schedule(int n_blocks, int n_nodes, int32_t* dest, i
  * time, 0 if some are spans between recorded events (or nothing was probed). */
 int ls_stage_probe_is_kernel_exact(const ls_stage* stage);
 
+/*
+ * Measurement aids, not part of the stage's path: what this GPU sustains for the two
+ * resources the path is bound by (the paper defines no such operation; bench.py reports
+ * fractions of the published peaks and of these).
+ * ls_probe_read_gbps: streams `bytes` (>= 16, a multiple of 16 is used) of the device buffer
+ *   `buf` (16-byte aligned, only read) with the 16-byte non-temporal loads of the decode
+ *   kernels, `reps` times after a warm-up; returns the GB/s of the fastest repetition.
+ * ls_probe_mfma_tflops: every SIMD runs `iters` x 8 independent v_mfma_f32_32x32x16_bf16 from
+ *   registers; returns the dense bf16 TFLOP/s of the fastest of `reps` repetitions.
+ * `sink` is a device pointer to at least 4 writable bytes or NULL (the kernels never write it
+ * in practice; it keeps their work from being optimised away).  Both block until done and
+ * return a negative value on bad arguments or a HIP error (see ls_last_error).
+ */
+double ls_probe_read_gbps(const void* buf, size_t bytes, int reps, void* sink, void* hip_stream);
+double ls_probe_mfma_tflops(int iters, int reps, void* sink, void* hip_stream);
+
 /* Message of the last failing call on this thread ("" if none). */
 const char* ls_last_error(void);
 

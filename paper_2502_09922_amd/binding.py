@@ -92,6 +92,8 @@ _SIGS = {
     "ls_plan_pipelines": (C.c_int, [C.POINTER(C.c_int32), C.c_int, C.POINTER(C.c_int32), C.POINTER(C.c_int32),
                                     C.POINTER(C.c_int32), C.c_int, C.POINTER(C.c_int)]),
     "ls_plan_multicast_steps": (C.c_int, [C.c_int, C.c_int]),
+    "ls_probe_read_gbps": (C.c_double, [C.c_void_p, C.c_size_t, C.c_int, C.c_void_p, C.c_void_p]),
+    "ls_probe_mfma_tflops": (C.c_double, [C.c_int, C.c_int, C.c_void_p, C.c_void_p]),
     "ls_plan_multicast_schedule": (C.c_int, [C.c_int, C.c_int, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.c_int,
                                              C.POINTER(C.c_int)]),
     "ls_last_error": (C.c_char_p, []),

@@ -274,3 +274,22 @@ def test_coarse_blocks_of_several_layers_equal_per_layer_blocks():
     torch.cuda.synchronize()
     assert torch.equal(got_lg, ref_lg) and torch.equal(got_tok, ref_tok)
     st.close(); pre.close()
+
+
+def test_measurement_probes_report_plausible_rates():
+    """The roofline aids of bench.py: a streaming read and a register-only MFMA loop.  Their
+    values are machine properties; the test only fixes that they run and land above a tenth
+    of the published peaks (8 TB/s, 2.5 PFLOP/s) and, for the MFMA loop, not above the peak
+    (a 256 MB buffer may be served from the memory-side cache, so the read has no upper bound here)."""
+    import ctypes as C
+    import torch
+    from paper_2502_09922_amd import binding as b
+
+    buf = torch.ones(1 << 28, dtype=torch.uint8, device="cuda")
+    sink = torch.zeros(4, dtype=torch.float32, device="cuda")
+    st = C.c_void_p(torch.cuda.current_stream().cuda_stream)
+    read = b.ls_probe_read_gbps(C.c_void_p(buf.data_ptr()), buf.numel(), 2, C.c_void_p(sink.data_ptr()), st)
+    mfma = b.ls_probe_mfma_tflops(500, 2, C.c_void_p(sink.data_ptr()), st)
+    assert 800.0 < read < 1e5, read
+    assert 250.0 < mfma <= 2500.0 * 1.02, mfma
+    assert float(sink.sum()) == 0.0 and int(buf[:64].sum()) == 64  # neither buffer was written

@@ -109,3 +109,13 @@ def test_pipeline_argument_errors_need_no_gpu():
     assert b.ls_pipeline_run(None, 0, None, 1, None) == b.LS_ERR_INVALID_ARG
     assert b.ls_stage_info(None, None, None, None) == b.LS_ERR_INVALID_ARG
     b.ls_pipeline_destroy(None)  # a no-op
+
+
+def test_measurement_probes_reject_bad_arguments_without_a_gpu():
+    assert b.ls_probe_read_gbps(None, 1 << 20, 1, None, None) < 0
+    assert b.ls_probe_read_gbps(C.c_void_p(4096), 8, 1, None, None) < 0      # fewer than 16 bytes
+    assert b.ls_probe_read_gbps(C.c_void_p(4100), 1 << 20, 1, None, None) < 0  # not 16-byte aligned
+    assert b.ls_probe_read_gbps(C.c_void_p(4096), 1 << 20, 0, None, None) < 0
+    assert b.ls_probe_mfma_tflops(0, 1, None, None) < 0
+    assert b.ls_probe_mfma_tflops(10, 0, None, None) < 0
+    assert b"ls_probe" in b.lib.ls_last_error()
