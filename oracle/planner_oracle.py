@@ -39,23 +39,24 @@ def subgroup_sizes(n_nodes, k):
 
 def pipelines(sizes):
     """sizes[i] = nodes of sub-group i that can join a pipeline.  Returns the pipelines in
-    the order they are formed, each a list of (sub-group, node index inside it)."""
-    used = [0] * len(sizes)
-    out = []
-    while True:
-        live = [i for i in range(len(sizes)) if used[i] < sizes[i]]
-        if not live:
-            return out
-        if len(live) == 1:
-            g = live[0]
-            out.append([(g, j) for j in range(used[g], sizes[g])])
-            used[g] = sizes[g]
-            continue
-        a = min(sizes[i] - used[i] for i in live)
-        for _ in range(a):
-            out.append([(i, used[i]) for i in live])
-            for i in live:
-                used[i] += 1
+    the order they are formed, each a list of (sub-group, node index inside it).
+
+    Stated by depth instead of by rounds: a pipeline takes one node from every sub-group that
+    still has one, and nodes join in index order, so the t-th pipeline is made of the t-th
+    node of every sub-group holding more than t nodes -- as long as at least two sub-groups
+    reach that depth.  Beyond it at most one sub-group has nodes left, and those form one
+    last pipeline among themselves."""
+    def at_depth(t):
+        return [(i, t) for i, n in enumerate(sizes) if n > t]
+
+    out, t = [], 0
+    while len(at_depth(t)) >= 2:
+        out.append(at_depth(t))
+        t += 1
+    rest = [(i, j) for i, n in enumerate(sizes) for j in range(t, n)]
+    if rest:
+        out.append(rest)
+    return out
 
 
 def multicast_steps(b, n_nodes):

@@ -22,7 +22,9 @@ used as a library step for the projections and for score/value products.
 Pins (tests/test_oracle_pins.py): RMSNorm closed forms, RoPE invariants,
 attention against a literal triple loop and special cases, matmul orientation
 against explicit loops, SwiGLU special values, layer identity cases,
-prefill/decode KV consistency, ragged-vs-alone, split invariance, argmax ties.
+prefill/decode KV consistency, ragged-vs-alone, split invariance, argmax ties,
+the final norm + LM head against scalar loops and a closed form, the embedding
+and head block layouts against hand-computed offsets.
 End-to-end values are "parity unpinned" against any published number: the paper
 prints none for this path.
 """
@@ -160,6 +162,15 @@ def silu(z: np.ndarray) -> np.ndarray:
     return z / (1.0 + np.exp(-z))
 
 
+def head_logits(x: np.ndarray, gamma: np.ndarray, w_head: np.ndarray, eps: float) -> np.ndarray:
+    """Final norm and LM head: logits[r, v] = sum_i RMSNorm(x[r]; gamma)_i * w_head[v, i].
+
+    x [rows, d] is the residual stream after the last layer at the rows that
+    produce a token; w_head is [vocab, d] (row-major [out, in] like every matrix).
+    """
+    return rmsnorm(x, gamma, eps) @ w_head.T
+
+
 def greedy(logits: np.ndarray) -> np.ndarray:
     """argmax per row; the lowest index wins a tie."""
     return np.argmax(logits, axis=-1).astype(np.int32)
@@ -243,7 +254,7 @@ class OracleStage:
         if not self.last:
             return x
         wl = self.w[s.n_layers_total]
-        logits = rmsnorm(x[last_rows], wl["final_norm"], s.rms_eps) @ wl["lm_head"].T
+        logits = head_logits(x[last_rows], wl["final_norm"], wl["lm_head"], s.rms_eps)
         return greedy(logits), logits
 
     # -- entry points ---------------------------------------------------------

@@ -359,6 +359,121 @@ def test_packed_equals_unpacked():
     np.testing.assert_array_equal(a.prefill(x, [6]), b.prefill(x, [6]))
 
 
+
+# ----------------------------------------------------------------------------- final norm + LM head, small blocks
+def identity_layers(st):
+    """Zero the output and down projections: every layer leaves the residual stream alone."""
+    for l in range(st.lo, st.hi):
+        st.w[l] = {k: np.zeros_like(v) if k in ("wo", "wd") else v for k, v in st.w[l].items()}
+    return st
+
+
+def test_head_leg_against_scalar_loops_on_a_ragged_batch():
+    """With identity layers the stage is embedding -> final norm -> LM head at the LAST row of
+    every sequence; each logit is recomputed with plain Python loops from the raw tensors."""
+    s = TINY
+    st = identity_layers(make_stage(s))
+    lens = [3, 1, 4]
+    tok = synth.token_ids(21, sum(lens), s.vocab)
+    nt, lg = st.prefill(tok, lens)
+    E = so.decode_values(synth.embed_tensors(s, 5)["embed"])
+    head = synth.head_tensors(s, 5)
+    g, W = so.decode_values(head["final_norm"]), so.decode_values(head["lm_head"])
+    assert lg.shape == (3, s.vocab)
+    for b, last in enumerate([2, 3, 7]):  # rows of the packed batch that end a sequence
+        x = [float(E[int(tok[last]), i]) for i in range(s.hidden)]
+        ms = sum(v * v for v in x) / s.hidden
+        y = [x[i] / math.sqrt(ms + s.rms_eps) * float(g[i]) for i in range(s.hidden)]
+        for v in range(s.vocab):
+            want = sum(y[i] * float(W[v, i]) for i in range(s.hidden))
+            assert abs(lg[b, v] - want) <= 1e-12 * max(1.0, abs(want)), (b, v)
+        assert int(nt[b]) == max(range(s.vocab), key=lambda v: (lg[b, v], -v))
+    # a decode step takes the one new row of every sequence
+    nt2, lg2 = st.decode(nt)
+    for b in range(3):
+        x = E[int(nt[b])]
+        y = x / math.sqrt(float(np.mean(x * x)) + s.rms_eps) * g
+        np.testing.assert_allclose(lg2[b], [float(np.dot(y, W[v])) for v in range(s.vocab)], rtol=1e-12, atol=1e-15)
+
+
+def test_head_leg_closed_form_gain_and_orientation():
+    """x = (3, 4, 0, ...) over d = 16, eps = 0: rms = 1.25, so the normalised row is (2.4, 3.2, 0, ...)
+    times the gain.  The head is a shift, logits[v] = y[(v + 1) mod 16]: its transpose would
+    shift the other way, a missing gain would leave 2.4 / 3.2 and move the argmax."""
+    s = TINY.with_(vocab=16, rms_eps=0.0)
+    gain = np.full(16, 1.0)
+    gain[0], gain[1] = 1.5, 0.25
+    shift = np.zeros((16, 16))
+    for v in range(16):
+        shift[v, (v + 1) % 16] = 1.0
+    x = np.zeros((1, 16))
+    x[0, 0], x[0, 1] = 3.0, 4.0
+    lg = so.head_logits(x, gain, shift, 0.0)
+    want = np.zeros(16)
+    want[15], want[0] = 2.4 * 1.5, 3.2 * 0.25  # y0 lands on v = 15, y1 on v = 0
+    np.testing.assert_allclose(lg[0], want, rtol=1e-15, atol=1e-15)
+    # the same through the stage: token 7's embedding row is x, layers are identity
+    st = identity_layers(make_stage(s))
+    emb = rnd(8, 16, 16)
+    emb[7] = x[0]
+    st.w[-1] = {"embed": emb}
+    st.w[s.n_layers_total] = {"final_norm": gain, "lm_head": shift}
+    nt, lg = st.prefill(np.array([2, 7], np.int32), [2])
+    np.testing.assert_allclose(lg[0], want, rtol=1e-15, atol=1e-15)
+    assert nt.tolist() == [15]
+    # eps sits inside the root here too: x = (3, 4, 0...) with eps = 9/16 gives rms = sqrt(25/16 + 9/16)
+    lg_eps = so.head_logits(x, np.ones(16), np.eye(16), 9.0 / 16.0)
+    np.testing.assert_allclose(lg_eps[0, :2], [3.0 / math.sqrt(34.0 / 16.0), 4.0 / math.sqrt(34.0 / 16.0)], rtol=1e-15)
+
+
+def test_embed_and_head_block_layouts_hand_computed():
+    # tiny fp32 benchmark config: V = 512, d = 256, 4-byte elements
+    tiny = synth.CONFIGS["tiny_f32"]
+    lay = so.embed_block_layout(tiny)
+    assert lay["embed"] == (0, (512, 256)) and lay["__bytes__"][0] == 524288
+    lay = so.head_block_layout(tiny)
+    assert lay["final_norm"] == (0, (256,))
+    assert lay["lm_head"] == (1024, (512, 256))
+    assert lay["__bytes__"][0] == 1024 + 524288
+    # bf16, d = 20, V = 50: the 40-byte gain is padded to 256; 50*20*2 = 2000 bytes pad to 2048
+    odd = synth.StageShape("bf16", 1, 20, 2, 1, 4, 10, 50)
+    lay = so.head_block_layout(odd)
+    assert lay["final_norm"] == (0, (20,)) and lay["lm_head"] == (256, (50, 20))
+    assert lay["__bytes__"][0] == 256 + 2048
+    assert so.embed_block_layout(odd)["__bytes__"][0] == 2048
+    # Llama-13B-shaped head: 5120 gains (10240 B, already aligned) + 32000 x 5120 bf16
+    big = so.head_block_layout(synth.CONFIGS["llama13b"])
+    assert big["lm_head"][0] == 10240 and big["__bytes__"][0] == 10240 + 32000 * 5120 * 2
+
+
+def test_embed_and_head_blocks_load_from_packed_bytes():
+    """load_block(-1) and load_block(L) on buffers assembled at hand-computed offsets (padding
+    filled with junk) give the stage the same tensors as handing them over unpacked."""
+    s = synth.StageShape("bf16", 1, 20, 2, 1, 4, 10, 50)
+    e, h = synth.embed_tensors(s, 9), synth.head_tensors(s, 9)
+    ebuf = np.full(2048, 0xAB, np.uint8)
+    ebuf[:2000] = e["embed"].view(np.uint8).reshape(-1)
+    hbuf = np.full(256 + 2048, 0xCD, np.uint8)
+    hbuf[:40] = h["final_norm"].view(np.uint8).reshape(-1)
+    hbuf[256:2256] = h["lm_head"].view(np.uint8).reshape(-1)
+    a, b = so.OracleStage(s, 0, 1, 2, 8), so.OracleStage(s, 0, 1, 2, 8)
+    for st in (a, b):
+        st.load_tensors(0, synth.layer_tensors(s, 9, 0))
+    a.load_block(-1, ebuf)
+    a.load_block(1, hbuf)
+    b.load_tensors(-1, e)
+    b.load_tensors(1, h)
+    np.testing.assert_array_equal(a.w[-1]["embed"], so.decode_values(e["embed"]))
+    np.testing.assert_array_equal(a.w[1]["final_norm"], so.decode_values(h["final_norm"]))
+    np.testing.assert_array_equal(a.w[1]["lm_head"], so.decode_values(h["lm_head"]))
+    tok = synth.token_ids(3, 5, s.vocab)
+    (ta, la), (tb, lb) = a.prefill(tok, [2, 3]), b.prefill(tok, [2, 3])
+    np.testing.assert_array_equal(la, lb)
+    assert ta.tolist() == tb.tolist()
+    with pytest.raises(AssertionError):  # a block of the wrong size is refused
+        a.load_block(1, hbuf[:-256])
+
+
 # ----------------------------------------------------------------------------- planted mistakes
 def _run_pins():
     for fn in (
@@ -372,6 +487,10 @@ def _run_pins():
         test_layer_identity_and_closed_form_cases,
         test_prefill_equals_shorter_prefill_plus_decode,
         test_split_invariance_and_last_position_logits,
+        test_head_leg_against_scalar_loops_on_a_ragged_batch,
+        test_head_leg_closed_form_gain_and_orientation,
+        test_embed_and_head_block_layouts_hand_computed,
+        test_embed_and_head_blocks_load_from_packed_bytes,
     ):
         fn()
 
@@ -406,8 +525,34 @@ def test_planted_mistakes_are_caught(monkeypatch):
     def greedy_last(lg):
         return (lg.shape[-1] - 1 - np.argmax(lg[..., ::-1], -1)).astype(np.int32)
 
-    so_rope, so_attn = so.rope, so.attention_rows
+    def head_without_norm(x, g, w, eps):
+        return x @ w.T
+
+    def head_without_gain(x, g, w, eps):
+        return so_rms(x, np.ones_like(g), eps) @ w.T
+
+    def head_transposed(x, g, w, eps):
+        return so_rms(x, g, eps) @ (w if w.shape[0] == w.shape[1] else w.T)
+
+    def head_eps_outside(x, g, w, eps):
+        return x / (np.sqrt(np.mean(x * x, -1, keepdims=True)) + eps) * g @ w.T
+
+    def head_layout_unpadded(s):
+        isz = 4 if s.dtype == "f32" else 2
+        return {"final_norm": (0, (s.hidden,)), "lm_head": (s.hidden * isz, (s.vocab, s.hidden)),
+                "__bytes__": (so_round(s.hidden * isz + s.vocab * s.hidden * isz, 256), ())}
+
+    def head_layout_swapped(s):
+        isz = 4 if s.dtype == "f32" else 2
+        nh = so_round(s.vocab * s.hidden * isz, 256)
+        return {"lm_head": (0, (s.vocab, s.hidden)), "final_norm": (nh, (s.hidden,)),
+                "__bytes__": (nh + so_round(s.hidden * isz, 256), ())}
+
+    so_rope, so_attn, so_rms, so_round = so.rope, so.attention_rows, so.rmsnorm, so._round_up
     plants = [
+        ("head_logits", head_without_norm), ("head_logits", head_without_gain),
+        ("head_logits", head_transposed), ("head_logits", head_eps_outside),
+        ("head_block_layout", head_layout_unpadded), ("head_block_layout", head_layout_swapped),
         ("rope", rope_half_split), ("rope", rope_wrong_sign), ("rmsnorm", rmsnorm_eps_outside),
         ("attention_rows", attn_no_scale), ("attention_rows", attn_strict_causal),
         ("attention_rows", attn_wrong_group), ("silu", silu_as_sigmoid), ("greedy", greedy_last),
