@@ -216,6 +216,16 @@ ls_status ls_stage_prefill(ls_stage* stage, const void* in, const int32_t* cu_se
 ls_status ls_stage_decode(ls_stage* stage, const void* in, int batch, int max_ctx,
                           const ls_kv* kv, void* out, float* logits_out, void* hip_stream);
 
+/*
+ * Host-only validation: what ls_stage_prefill / ls_stage_decode would reject from their shape
+ * arguments and the stage's own state (batch and token limits, cu_seqlens well-formed, every
+ * block enqueued for load), without touching the device.  ls_pipeline_run calls these for
+ * every (stage, micro-batch) before it enqueues anything (Section 4.3: a batch passes through
+ * every stage of its pipeline, so a pass is all-or-nothing).
+ */
+ls_status ls_stage_check_prefill(const ls_stage* stage, const int32_t* cu_seqlens_host, int batch, int total_tokens);
+ls_status ls_stage_check_decode(const ls_stage* stage, int batch, int max_ctx);
+
 /* ---- measurement ---------------------------------------------------------------------*/
 
 /* With profiling on, ls_stage_load_block brackets each copy and ls_stage_prefill brackets
@@ -232,6 +242,17 @@ ls_status ls_stage_set_profiling(ls_stage* stage, int on);
  */
 ls_status ls_stage_layer_times(ls_stage* stage, float* copy_ms, float* compute_ms,
                                float* copy_end_ms, float* compute_end_ms, int n);
+
+/* After the caller has synchronised: duration of block `layer`'s last copy (any block the stage
+ * holds, the embedding and head blocks included) and its completion time relative to the
+ * start of the first copy made with profiling on since the last reset (either may be NULL). */
+ls_status ls_stage_block_times(ls_stage* stage, int layer, float* copy_ms, float* copy_end_ms);
+
+/* After the caller has synchronised: of the last prompt pass made with profiling on, the time
+ * before its first decoder layer started (row maps, embedding gather or input conversion),
+ * the time after its last decoder layer ended (final norm, LM head, argmax or output
+ * conversion) and the whole pass (any pointer may be NULL). */
+ls_status ls_stage_pass_times(ls_stage* stage, float* before_layers_ms, float* after_layers_ms, float* total_ms);
 
 /* Operators of one decoder layer that ls_stage_probe can time. */
 #define LS_OP_NONE 0
@@ -305,10 +326,9 @@ void ls_pipeline_destroy(ls_pipeline* pipe);
  * buffer of (stage s, micro-batch m) may be reused by the next call: stage s does not
  * overwrite it before stage s+1 has consumed the previous content (event wait).  `in`, `out`
  * and the caches are not guarded across calls: reuse them only in stream order of the first
- * / last stage's stream.  Argument errors that the host can see are reported before anything
- * is enqueued; an error that depends on a stage's own state (a block not yet enqueued for
- * load: LS_ERR_NOT_LOADED) is reported by that stage's call, after earlier stages of the
- * same micro-batch have been enqueued.  Only enqueues; never waits for the GPU.
+ * / last stage's stream.  Every error the host can see -- arguments, malformed cu_seqlens, a
+ * stage with a block not yet enqueued for load (LS_ERR_NOT_LOADED) -- is reported before
+ * anything is enqueued, for all stages and micro-batches.  Only enqueues; never waits for the GPU.
  */
 ls_status ls_pipeline_run(ls_pipeline* pipe, int phase, const ls_microbatch* mbs, int n_micro,
                           void* const* hip_streams);
@@ -362,6 +382,23 @@ int ls_plan_multicast_steps(int n_blocks, int n_nodes);
  */
 ls_status ls_plan_multicast_schedule(int n_blocks, int n_nodes, int32_t* dest, int32_t* block, int capacity_steps,
                                      int* n_steps);
+
+/*
+ * Where an intermediate result of the forward pass lies inside the caller's workspace, so that
+ * a test can compare single operators with a reference: after a call has completed, the
+ * region holds what the stage's LAST layer left there.  Row-major, `dtype` elements, one row
+ * per row of the call:
+ *   LS_WS_QKV   [rows, (Hq+2Hkv)*hd]  projections y Wqkv^T; after a prompt pass the query part
+ *               is rotated (RoPE) in place, the key/value parts are as projected (the rotated
+ *               keys are in the cache); after a generation step all parts are as projected
+ *   LS_WS_ATTN  [rows, Hq*hd]         attention output, heads side by side
+ *   LS_WS_FFN   [rows, F]             silu(y Wg^T) * (y Wu^T)
+ * *offset / *bytes: position and size (at the cfg's limits) inside the workspace.
+ */
+#define LS_WS_QKV 1
+#define LS_WS_ATTN 2
+#define LS_WS_FFN 3
+ls_status ls_stage_workspace_region(const ls_stage* stage, int which, size_t* offset, size_t* bytes);
 
 /* 1 if every duration ls_stage_probe_times would return now is a kernel's own start-to-stop
  * time, 0 if some are spans between recorded events (or nothing was probed). */

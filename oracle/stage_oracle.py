@@ -27,6 +27,17 @@ the final norm + LM head against scalar loops and a closed form, the embedding
 and head block layouts against hand-computed offsets.
 End-to-end values are "parity unpinned" against any published number: the paper
 prints none for this path.
+
+Diagnostic mode (not the parity bar).  OracleStage(..., bf16_handoffs=True) rounds
+to bfloat16 (nearest even) at the places where a 16-bit pipeline of this layer
+must store an activation in its 16-bit type: the normalised rows that feed a
+projection, the q/k/v projections, the rotated q and k, the softmax weights
+that multiply the values, the attention output, the SwiGLU output, and the
+stage's hidden-state output.  Everything else stays float64.  Random-weight
+decoders of this recipe amplify a relative perturbation from layer to layer, so
+at depths of tens of layers ANY 16-bit pipeline drifts from the float64 result
+by more than its per-layer error; this mode tells that arithmetic drift (it
+shows the same drift) from a defect in a kernel (it would not).
 """
 from __future__ import annotations
 
@@ -47,6 +58,13 @@ def decode_values(a: np.ndarray) -> np.ndarray:
     if a.dtype == np.uint16:
         return (a.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
     return a.astype(np.float64)
+
+
+def round_bf16(a: np.ndarray) -> np.ndarray:
+    """float64 -> nearest bfloat16 (ties to even) -> float64; used by the diagnostic mode only."""
+    u = np.ascontiguousarray(a, dtype=np.float32).view(np.uint32)
+    u = (u + (((u >> np.uint32(16)) & np.uint32(1)) + np.uint32(0x7FFF))) & np.uint32(0xFFFF0000)
+    return u.view(np.float32).astype(np.float64)
 
 
 def _round_up(n: int, m: int) -> int:
@@ -135,13 +153,14 @@ def rope(u: np.ndarray, pos: np.ndarray, base: float) -> np.ndarray:
     return out
 
 
-def attention_rows(q: np.ndarray, k: np.ndarray, v: np.ndarray, pos: np.ndarray) -> np.ndarray:
+def attention_rows(q: np.ndarray, k: np.ndarray, v: np.ndarray, pos: np.ndarray, round_weights=None) -> np.ndarray:
     """Causal softmax attention of one sequence.
 
     q   [n, Hq, hd]   the n query rows, row r at absolute position pos[r]
     k,v [Hkv, ctx, hd] cached keys / values at positions 0..ctx-1
     Query head h reads kv head h // (Hq/Hkv).  Key j is visible to row r iff
-    j <= pos[r].  Scores are scaled by 1/sqrt(hd).
+    j <= pos[r].  Scores are scaled by 1/sqrt(hd).  round_weights (diagnostic mode
+    only) is applied to the un-normalised softmax weights that multiply v.
     """
     n, hq, hd = q.shape
     hkv, ctx, _ = k.shape
@@ -153,8 +172,11 @@ def attention_rows(q: np.ndarray, k: np.ndarray, v: np.ndarray, pos: np.ndarray)
         s = np.where(visible, s, -np.inf)
         s = s - s.max(axis=-1, keepdims=True)
         p = np.exp(s)
-        p = p / p.sum(axis=-1, keepdims=True)
-        out[:, h, :] = p @ v[h // g]
+        if round_weights is None:
+            p = p / p.sum(axis=-1, keepdims=True)
+            out[:, h, :] = p @ v[h // g]
+        else:
+            out[:, h, :] = (round_weights(p) @ v[h // g]) / p.sum(axis=-1, keepdims=True)
     return out
 
 
@@ -190,8 +212,12 @@ class OracleStage:
     stream after its last layer, un-normalised.
     """
 
-    def __init__(self, s, layer_lo: int, layer_hi: int, max_batch: int, max_seq: int):
+    def __init__(self, s, layer_lo: int, layer_hi: int, max_batch: int, max_seq: int, bf16_handoffs: bool = False):
         assert 0 <= layer_lo < layer_hi <= s.n_layers_total
+        # diagnostic mode (see the file header): identity unless switched on
+        self._r = round_bf16 if bf16_handoffs else (lambda a: a)
+        self._rw = round_bf16 if bf16_handoffs else None
+        self.round_output = bf16_handoffs  # a middle stage's hidden-state output is stored in 16 bits too
         self.s, self.lo, self.hi = s, layer_lo, layer_hi
         self.first = s.vocab > 0 and layer_lo == 0
         self.last = s.vocab > 0 and layer_hi == s.n_layers_total
@@ -222,13 +248,14 @@ class OracleStage:
     def _layer(self, li: int, x: np.ndarray, seq_of_row, pos, rows_of_seq) -> np.ndarray:
         s, w = self.s, self.w[self.lo + li]
         hq, hkv, hd = s.n_q_heads, s.n_kv_heads, s.head_dim
-        y = rmsnorm(x, w["attn_norm"], s.rms_eps)
-        qkv = y @ w["wqkv"].T
+        r = self._r
+        y = r(rmsnorm(x, w["attn_norm"], s.rms_eps))
+        qkv = r(y @ w["wqkv"].T)
         q = qkv[:, : hq * hd].reshape(-1, hq, hd)
         k = qkv[:, hq * hd : (hq + hkv) * hd].reshape(-1, hkv, hd)
         v = qkv[:, (hq + hkv) * hd :].reshape(-1, hkv, hd)
-        q = rope(q, pos, s.rope_base)
-        k = rope(k, pos, s.rope_base)
+        q = r(rope(q, pos, s.rope_base))
+        k = r(rope(k, pos, s.rope_base))
         # append to the cache, then attend over everything cached so far
         sq = np.asarray(seq_of_row)
         self.k[li, sq, :, pos, :] = k  # row r goes to [li, seq r, every kv head, pos r, :]
@@ -236,11 +263,11 @@ class OracleStage:
         o = np.empty_like(q)
         for b, rows in rows_of_seq.items():
             ctx = int(pos[rows[-1]]) + 1
-            o[rows] = attention_rows(q[rows], self.k[li, b, :, :ctx], self.v[li, b, :, :ctx], pos[rows])
-        x = x + o.reshape(-1, hq * hd) @ w["wo"].T
-        y = rmsnorm(x, w["ffn_norm"], s.rms_eps)
+            o[rows] = attention_rows(q[rows], self.k[li, b, :, :ctx], self.v[li, b, :, :ctx], pos[rows], self._rw)
+        x = x + r(o).reshape(-1, hq * hd) @ w["wo"].T
+        y = r(rmsnorm(x, w["ffn_norm"], s.rms_eps))
         gu = y @ w["wgu"].T
-        h = silu(gu[:, : s.ffn]) * gu[:, s.ffn :]
+        h = r(silu(gu[:, : s.ffn]) * gu[:, s.ffn :])
         return x + h @ w["wd"].T
 
     def _run(self, inp, seq_of_row, pos, rows_of_seq, last_rows):
@@ -252,8 +279,11 @@ class OracleStage:
         for li in range(self.hi - self.lo):
             x = self._layer(li, x, seq_of_row, pos, rows_of_seq)
         if not self.last:
-            return x
+            return round_bf16(x) if self.round_output else x
         wl = self.w[s.n_layers_total]
+        if self._rw is not None:  # diagnostic mode: the normalised rows are stored in 16 bits
+            logits = self._r(rmsnorm(x[last_rows], wl["final_norm"], s.rms_eps)) @ wl["lm_head"].T
+            return greedy(logits), logits
         logits = head_logits(x[last_rows], wl["final_norm"], wl["lm_head"], s.rms_eps)
         return greedy(logits), logits
 

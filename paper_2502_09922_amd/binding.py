@@ -31,6 +31,7 @@ LS_ABI_VERSION = 1
 LS_DTYPE_F32, LS_DTYPE_BF16 = 0, 1
 LS_BLOCK_EMBED = -1
 LS_OP_NONE, LS_OP_NORM, LS_OP_GEMM_QKV = 0, 1, 2
+LS_WS_QKV, LS_WS_ATTN, LS_WS_FFN = 1, 2, 3
 LS_OP_ATTENTION, LS_OP_GEMM_O, LS_OP_GEMM_GATEUP, LS_OP_GEMM_DOWN = 4, 5, 6, 7
 (LS_OK, LS_ERR_INVALID_ARG, LS_ERR_BLOCK_RANGE, LS_ERR_NOT_LOADED, LS_ERR_ALREADY_LOADED,
  LS_ERR_KV_OVERFLOW, LS_ERR_OOM, LS_ERR_HIP) = (0, -1, -2, -3, -4, -5, -6, -7)
@@ -77,11 +78,16 @@ _SIGS = {
     "ls_stage_reset_blocks": (C.c_int, [_P]),
     "ls_stage_prefill": (C.c_int, [_P, _P, _P, C.POINTER(C.c_int32), C.c_int, C.c_int, C.POINTER(ls_kv), _P, _P, _P]),
     "ls_stage_decode": (C.c_int, [_P, _P, C.c_int, C.c_int, C.POINTER(ls_kv), _P, _P, _P]),
+    "ls_stage_check_prefill": (C.c_int, [_P, C.POINTER(C.c_int32), C.c_int, C.c_int]),
+    "ls_stage_check_decode": (C.c_int, [_P, C.c_int, C.c_int]),
     "ls_stage_set_profiling": (C.c_int, [_P, C.c_int]),
     "ls_stage_layer_times": (C.c_int, [_P, C.POINTER(C.c_float), C.POINTER(C.c_float), C.POINTER(C.c_float), C.POINTER(C.c_float), C.c_int]),
+    "ls_stage_block_times": (C.c_int, [_P, C.c_int, C.POINTER(C.c_float), C.POINTER(C.c_float)]),
+    "ls_stage_pass_times": (C.c_int, [_P, C.POINTER(C.c_float), C.POINTER(C.c_float), C.POINTER(C.c_float)]),
     "ls_stage_probe": (C.c_int, [_P, C.c_int, C.c_int, C.c_int]),
     "ls_stage_probe_times": (C.c_int, [_P, C.POINTER(C.c_float), C.c_int, C.POINTER(C.c_int)]),
     "ls_stage_probe_is_kernel_exact": (C.c_int, [_P]),
+    "ls_stage_workspace_region": (C.c_int, [_P, C.c_int, C.POINTER(C.c_size_t), C.POINTER(C.c_size_t)]),
     "ls_stage_info": (C.c_int, [_P, C.POINTER(ls_cfg), C.POINTER(C.c_int), C.POINTER(C.c_int)]),
     "ls_pipeline_create": (C.c_int, [C.POINTER(_P), C.c_int, C.POINTER(_P)]),
     "ls_pipeline_destroy": (None, [_P]),
@@ -213,6 +219,26 @@ class Stage:
         """host: pinned uint8 tensor holding the packed blocks of layers first..last back to back."""
         check(lib.ls_stage_load_layers(self.handle, host.data_ptr(), first, last, self._stream_ptr(stream)))
 
+    def adopt_block(self, layer: int, stream=None):
+        """The packed bytes of block `layer` are already in the slab (written on `stream`)."""
+        check(lib.ls_stage_adopt_block(self.handle, layer, self._stream_ptr(stream)))
+
+    def block_view(self, layer: int):
+        """uint8 view of block `layer` inside the slab."""
+        ptr = lib.ls_stage_block_device_ptr(self.handle, layer)
+        off = ptr - self.slab.data_ptr()
+        return self.slab[off : off + lib.ls_stage_block_bytes(self.handle, layer)]
+
+    def block_times(self, layer: int):
+        a, b = C.c_float(), C.c_float()
+        check(lib.ls_stage_block_times(self.handle, layer, C.byref(a), C.byref(b)))
+        return a.value, b.value
+
+    def pass_times(self):
+        a, b, c = C.c_float(), C.c_float(), C.c_float()
+        check(lib.ls_stage_pass_times(self.handle, C.byref(a), C.byref(b), C.byref(c)))
+        return a.value, b.value, c.value
+
     def reset_blocks(self):
         check(lib.ls_stage_reset_blocks(self.handle))
 
@@ -235,15 +261,25 @@ class Stage:
 
     def decode(self, inp, batch: int, max_ctx: int, stream=None, want_logits=False, out=None):
         torch = self.torch
+        fn = lib.ls_stage_decode
         if out is None:
             out = (torch.empty(batch, dtype=torch.int32, device=self.device) if self.last
                    else torch.empty(batch, self.shape.hidden, dtype=self.tdtype, device=self.device))
         logits = (torch.empty(batch, self.shape.vocab, dtype=torch.float32, device=self.device)
                   if (want_logits and self.last) else None)
-        check(lib.ls_stage_decode(
+        check(fn(
             self.handle, inp.data_ptr(), batch, max_ctx, C.byref(self.kv), out.data_ptr(),
             logits.data_ptr() if logits is not None else None, self._stream_ptr(stream)))
         return (out, logits) if want_logits else out
+
+    def workspace_region(self, which: int, rows: int):
+        """[rows, columns] view of an intermediate result inside the workspace (see ls_stage.h)."""
+        off, nb = C.c_size_t(), C.c_size_t()
+        check(lib.ls_stage_workspace_region(self.handle, which, C.byref(off), C.byref(nb)))
+        esz = 4 if self.shape.dtype == "f32" else 2
+        cols = nb.value // (self.cfg.max_tokens * esz)
+        flat = self.workspace[off.value : off.value + rows * cols * esz].view(self.tdtype)
+        return flat.view(rows, cols)
 
     def probe(self, op: int, layer: int = 0, phase: int = 1):
         check(lib.ls_stage_probe(self.handle, op, layer, phase))

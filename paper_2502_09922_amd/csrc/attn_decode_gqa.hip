@@ -223,11 +223,8 @@ template <int NW>
 void launch_nw(const void* qkv, int qkv_stride, const float* cs, void* kc, void* vc, const int32_t* row_seq,
                const int32_t* row_pos, int rows, int hq, int hkv, int max_seq, void* out, hipStream_t st) {
   constexpr int SMEM = NW * 2 * TILE_BYTES;  // >= the merge area: NW * (32 + 16*128) floats
-  static bool attr_set = false;
-  if (!attr_set) {
-    (void)hipFuncSetAttribute((const void*)k_attn_decode_gqa<NW>, hipFuncAttributeMaxDynamicSharedMemorySize, SMEM);
-    attr_set = true;
-  }
+  static std::atomic<uint64_t> lds_allowed{0};
+  allow_dynamic_lds((const void*)k_attn_decode_gqa<NW>, SMEM, lds_allowed);
   dim3 grid(rows, hkv);
   k_attn_decode_gqa<NW><<<grid, NW * 64, SMEM, st>>>((const bf16*)qkv, qkv_stride, (const float2*)cs, (bf16*)kc,
                                                      (bf16*)vc, row_seq, row_pos, hq, hkv, hq / hkv, max_seq, (bf16*)out);

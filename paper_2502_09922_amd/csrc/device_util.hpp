@@ -3,6 +3,10 @@
 #include <hip/hip_runtime.h>
 #include <hip/hip_ext.h>
 
+#include <atomic>
+#include <cstdint>
+#include <mutex>
+
 #include "kernels.hpp"
 
 namespace ls {
@@ -19,6 +23,33 @@ inline void launch_kernel(void (*kernel)(KArgs...), dim3 grid, dim3 block, unsig
   } else {
     hipLaunchKernelGGL(kernel, grid, block, smem, st, static_cast<KArgs>(args)...);
   }
+}
+
+// Raise a kernel's dynamic-LDS limit, once per device (`done` holds one bit per device ordinal;
+// the attribute belongs to each device's copy of the kernel).  Safe from several threads: a
+// race only sets the same attribute twice.
+inline void allow_dynamic_lds(const void* kernel, int bytes, std::atomic<uint64_t>& done) {
+  int dev = 0;
+  (void)hipGetDevice(&dev);
+  const uint64_t bit = 1ull << (dev & 63);
+  if (done.load(std::memory_order_acquire) & bit) return;
+  (void)hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+  done.fetch_or(bit, std::memory_order_release);
+}
+
+// The same for a kernel whose LDS need varies with the shape: `allowed[device]` is the limit set
+// so far, raised (under a lock, so that a smaller request cannot overwrite a larger one) when a
+// launch needs more.
+inline void allow_dynamic_lds_up_to(const void* kernel, int bytes, std::atomic<int> (&allowed)[64]) {
+  static std::mutex m;
+  int dev = 0;
+  (void)hipGetDevice(&dev);
+  std::atomic<int>& a = allowed[dev & 63];
+  if (bytes <= a.load(std::memory_order_acquire)) return;
+  std::lock_guard<std::mutex> lock(m);
+  if (bytes <= a.load(std::memory_order_relaxed)) return;
+  (void)hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+  a.store(bytes, std::memory_order_release);
 }
 
 typedef __bf16 bf16;

@@ -220,11 +220,8 @@ k_gemm_mfma(const bf16* __restrict__ A, const bf16* __restrict__ W, int M, int N
 
 template <int EPI>
 void launch_t(const void* A, const void* W, int M, int N, int K, void* out, float* resid, hipStream_t st) {
-  static bool attr_set = false;
-  if (!attr_set) {
-    (void)hipFuncSetAttribute((const void*)k_gemm_mfma<EPI>, hipFuncAttributeMaxDynamicSharedMemorySize, SMEM_BYTES);
-    attr_set = true;
-  }
+  static std::atomic<uint64_t> lds_allowed{0};
+  allow_dynamic_lds((const void*)k_gemm_mfma<EPI>, SMEM_BYTES, lds_allowed);
   const int tiles_m = (M + BM - 1) / BM;
   const int ncols = (EPI == EPI_SWIGLU) ? BN / 2 : BN;
   const int tiles_n = (N + ncols - 1) / ncols;

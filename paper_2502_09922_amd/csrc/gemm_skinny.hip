@@ -244,11 +244,8 @@ void launch_kn(const void* X, const void* W, int M, int N, int K, void* out, flo
   const int scratch = KS * NW * 4096;
   const int ss_bytes = (NORM && MT == 1) ? M * ((fu.n_part + 255) / 256) * 1024 : 0;
   const int smem = scratch + ss_bytes + KS * NW * MT * 1024;
-  static int attr_bytes = 0;
-  if (smem > attr_bytes) {
-    (void)hipFuncSetAttribute((const void*)k_gemm_skinny<MT, EPI, KS, PF, NORM>, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
-    attr_bytes = smem;
-  }
+  static std::atomic<int> lds_allowed[64];
+  allow_dynamic_lds_up_to((const void*)k_gemm_skinny<MT, EPI, KS, PF, NORM>, smem, lds_allowed);
   launch_kernel(k_gemm_skinny<MT, EPI, KS, PF, NORM>, dim3(N / 16), dim3(KS * 64), smem, st, (const bf16*)X,
                 (const bf16*)W, M, N, K, out, resid, fu);
 }

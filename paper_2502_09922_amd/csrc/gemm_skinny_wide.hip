@@ -221,11 +221,8 @@ template <int MT, bool GLU>
 void launch_main(const void* X, const void* W, int M, int N, int K, float* part, int splits, int bps, hipStream_t st) {
   constexpr int NW = GLU ? 2 : 1;
   constexpr int smem = 2 * MT * 16 * 256 + WAVES * NW * 4096;
-  static bool attr_set = false;
-  if (!attr_set) {
-    (void)hipFuncSetAttribute((const void*)k_gemm_wide<MT, GLU>, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
-    attr_set = true;
-  }
+  static std::atomic<uint64_t> lds_allowed{0};
+  allow_dynamic_lds((const void*)k_gemm_wide<MT, GLU>, smem, lds_allowed);
   dim3 grid(N / 64, splits);
   k_gemm_wide<MT, GLU><<<grid, WAVES * 64, smem, st>>>((const bf16*)X, (const bf16*)W, M, N, K, part, bps);
 }

@@ -98,7 +98,6 @@ double ls_probe_read_gbps(const void* buf, size_t bytes, int reps, void* sink, v
       ls::set_last_error("ls_probe_read_gbps: HIP error");
       return -1.0;
     }
-    if (getenv("LS_PROBE_VERBOSE")) fprintf(stderr, "read probe: %d workgroups %.1f GB/s\n", wgs, (double)(n16 * 16) / (t * 1e-3) / 1e9);
     if (ms < 0 || t < ms) ms = t;
   }
   return (double)(n16 * 16) / (ms * 1e-3) / 1e9;

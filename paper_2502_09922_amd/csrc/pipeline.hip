@@ -11,6 +11,7 @@
 struct ls_pipeline {
   std::vector<ls_stage*> stages;
   ls_cfg cfg;
+  bool last_has_head;  // the last stage ends at the model's last layer and the model has a vocabulary
   // events of micro-batch slot m at boundary s (between stage s and s+1): [m][s]
   std::vector<std::vector<hipEvent_t>> produced, consumed;
   std::vector<std::vector<char>> consumed_valid;  // consumed[m][s] has been recorded
@@ -84,6 +85,7 @@ ls_status ls_pipeline_create(ls_stage* const* stages, int n_stages, ls_pipeline*
   if (!p) return fail(LS_ERR_OOM, "ls_pipeline_create: host allocation failed");
   p->stages.assign(stages, stages + n_stages);
   p->cfg = first;
+  p->last_has_head = first.vocab && prev_hi == (int)first.n_layers_total;
   *out = p;
   return LS_OK;
 }
@@ -106,24 +108,16 @@ ls_status ls_pipeline_run(ls_pipeline* p, int phase, const ls_microbatch* mbs, i
     for (int s = 0; s + 1 < ns; ++s)
       if (!mb.handoff[s]) return fail(LS_ERR_INVALID_ARG, "ls_pipeline_run: NULL hand-off buffer");
     for (int s = 0; s < ns; ++s) {
-      ls_cfg c{};
-      (void)ls_stage_info(p->stages[s], &c, nullptr, nullptr);
-      if (mb.batch < 1 || mb.batch > (int)c.max_batch)
-        return fail(LS_ERR_INVALID_ARG, "ls_pipeline_run: batch outside a stage's limit");
       if (!mb.kv[s].k || !mb.kv[s].v || !mb.kv[s].seq_lens)
         return fail(LS_ERR_INVALID_ARG, "ls_pipeline_run: NULL pointer inside an ls_kv");
-      if (phase == 0) {
-        if (!mb.cu_seqlens_dev || !mb.cu_seqlens_host)
-          return fail(LS_ERR_INVALID_ARG, "ls_pipeline_run: NULL cu_seqlens");
-        if (mb.total_tokens < mb.batch || mb.total_tokens > (int)c.max_tokens)
-          return fail(LS_ERR_INVALID_ARG, "ls_pipeline_run: total_tokens outside a stage's limit");
-        for (int b = 0; b < mb.batch; ++b)
-          if (mb.cu_seqlens_host[b + 1] - mb.cu_seqlens_host[b] > (int)c.max_seq)
-            return fail(LS_ERR_KV_OVERFLOW, "ls_pipeline_run: a sequence exceeds a stage's max_seq");
-      } else if (mb.max_ctx < 0 || mb.max_ctx + 1 > (int)c.max_seq) {
-        return fail(LS_ERR_KV_OVERFLOW, "ls_pipeline_run: context exceeds a stage's max_seq");
-      }
+      if (phase == 0 && !mb.cu_seqlens_dev) return fail(LS_ERR_INVALID_ARG, "ls_pipeline_run: NULL cu_seqlens");
+      // the stage's own checks of shape and state (limits, cu_seqlens, blocks enqueued for load)
+      const ls_status rc = phase == 0 ? ls_stage_check_prefill(p->stages[s], mb.cu_seqlens_host, mb.batch, mb.total_tokens)
+                                      : ls_stage_check_decode(p->stages[s], mb.batch, mb.max_ctx);
+      if (rc != LS_OK) return rc;
     }
+    if (mb.logits_out && !p->last_has_head)
+      return fail(LS_ERR_INVALID_ARG, "ls_pipeline_run: logits_out given but the last stage has no LM head");
   }
   ls_status rc = grow(p, n_micro);
   if (rc != LS_OK) return rc;

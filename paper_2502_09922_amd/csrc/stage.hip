@@ -182,6 +182,7 @@ struct ls_stage {
   bool compute_timed;
   int origin_block;  // first block copied with profiling on since the last reset, or -1
   std::vector<hipEvent_t> comp_start, comp_end;
+  hipEvent_t pass_start = nullptr, pass_end = nullptr;  // around a whole profiled prompt pass
   // kernel probe: event pairs around one operator of one layer, a ring of PROBE_CAP pairs
   int probe_op, probe_layer, probe_phase;
   size_t probe_count;
@@ -292,6 +293,8 @@ ls_status ls_stage_create(const ls_cfg* cfg, int lo, int hi, void* weight_slab, 
     for (auto e : s->probe_b) (void)hipEventDestroy(e);
     for (auto e : s->probe_ka) (void)hipEventDestroy(e);
     for (auto e : s->probe_kb) (void)hipEventDestroy(e);
+    if (s->pass_start) (void)hipEventDestroy(s->pass_start);
+    if (s->pass_end) (void)hipEventDestroy(s->pass_end);
     delete s;
   };
   for (auto& b : s->blocks) {
@@ -309,6 +312,11 @@ ls_status ls_stage_create(const ls_cfg* cfg, int lo, int hi, void* weight_slab, 
     }
     s->comp_start.push_back(a);
     s->comp_end.push_back(b);
+  }
+
+  if (hipEventCreate(&s->pass_start) != hipSuccess || hipEventCreate(&s->pass_end) != hipSuccess) {
+    cleanup();
+    return fail(LS_ERR_HIP, "ls_stage_create: hipEventCreate failed");
   }
 
   // cos/sin of pos * base^(-2i/hd), evaluated in double and stored as fp32 pairs
@@ -341,6 +349,8 @@ void ls_stage_destroy(ls_stage* s) {
   for (auto e : s->probe_b) (void)hipEventDestroy(e);
   for (auto e : s->probe_ka) (void)hipEventDestroy(e);
   for (auto e : s->probe_kb) (void)hipEventDestroy(e);
+  (void)hipEventDestroy(s->pass_start);
+  (void)hipEventDestroy(s->pass_end);
   delete s;
 }
 
@@ -444,8 +454,9 @@ ls_status ls_stage_set_profiling(ls_stage* s, int on) {
 // ---- the forward pass -------------------------------------------------------------------
 namespace {
 
+// `gsc`: where GEMM kernels that split K across workgroups put their partial tiles.
 ls_status forward(ls_stage* s, bool prefill, const void* in, const int32_t* cu_dev, int batch, int rows, int max_len,
-                  const ls_kv* kv, void* out, float* logits_out, hipStream_t st) {
+                  const ls_kv* kv, void* out, float* logits_out, hipStream_t st, const ls::GemmScratch& gsc) {
   using namespace ls;
   const ls_cfg& c = s->cfg;
   const uint32_t dt = c.dtype;
@@ -462,9 +473,6 @@ ls_status forward(ls_stage* s, bool prefill, const void* in, const int32_t* cu_d
   int32_t* row_seq = (int32_t*)(ws + s->w.row_seq);
   int32_t* row_pos = (int32_t*)(ws + s->w.row_pos);
   int32_t* last_rows = (int32_t*)(ws + s->w.last_rows);
-  GemmScratch gsc;
-  gsc.splitk = s->w.splitk_bytes ? (float*)(ws + s->w.splitk) : nullptr;
-  gsc.bytes = s->w.splitk_bytes;
   const bool timed = s->profiling && prefill;
   const bool probing = s->probe_op != LS_OP_NONE && s->probe_phase == (prefill ? 0 : 1) && !s->probe_a.empty();
 
@@ -560,6 +568,7 @@ ls_status forward(ls_stage* s, bool prefill, const void* in, const int32_t* cu_d
     return LS_OK;
   }
 
+  if (timed) LS_HIP(hipEventRecord(s->pass_start, st));
   if (prefill) launch_row_index_prefill(cu_dev, batch, rows, row_seq, row_pos, last_rows, st);
   else launch_row_index_decode(kv->seq_lens, batch, c.max_seq, row_seq, row_pos, last_rows, st);
 
@@ -611,54 +620,98 @@ ls_status forward(ls_stage* s, bool prefill, const void* in, const int32_t* cu_d
 
   if (prefill) launch_seq_lens_set(cu_dev, batch, kv->seq_lens, st);
   else launch_seq_lens_inc(batch, c.max_seq, kv->seq_lens, st);
+  if (timed) LS_HIP(hipEventRecord(s->pass_end, st));
   LS_HIP(hipGetLastError());
   return LS_OK;
 }
 
-ls_status common_checks(const char* who, ls_stage* s, const void* in, int batch, const ls_kv* kv, void* out,
-                        float* logits_out) {
-  if (!s || !in || !kv || !out) return fail(LS_ERR_INVALID_ARG, "%s: NULL argument", who);
-  if (!kv->k || !kv->v || !kv->seq_lens) return fail(LS_ERR_INVALID_ARG, "%s: NULL pointer inside ls_kv", who);
+// ---- host-side validation: everything a forward call can reject before it enqueues ------
+ls_status check_state(const char* who, const ls_stage* s, int batch) {
+  if (!s) return fail(LS_ERR_INVALID_ARG, "%s: NULL stage", who);
   if (batch < 1 || batch > (int)s->cfg.max_batch)
     return fail(LS_ERR_INVALID_ARG, "%s: batch %d outside [1,%u]", who, batch, s->cfg.max_batch);
-  if (logits_out && !s->last) return fail(LS_ERR_INVALID_ARG, "%s: logits_out given but the stage has no LM head", who);
   for (const auto& b : s->blocks)
     if (b.state == NOT_LOADED) return fail(LS_ERR_NOT_LOADED, "%s: block %d has not been enqueued for load", who, b.layer);
   return LS_OK;
+}
+
+ls_status check_prefill(const char* who, const ls_stage* s, const int32_t* cu_host, int batch, int total_tokens,
+                        int* max_len_out) {
+  ls_status rc = check_state(who, s, batch);
+  if (rc != LS_OK) return rc;
+  if (!cu_host) return fail(LS_ERR_INVALID_ARG, "%s: NULL cu_seqlens", who);
+  if (total_tokens < batch || total_tokens > (int)s->cfg.max_tokens)
+    return fail(LS_ERR_INVALID_ARG, "%s: total_tokens %d outside [%d,%u]", who, total_tokens, batch, s->cfg.max_tokens);
+  if (cu_host[0] != 0 || cu_host[batch] != total_tokens)
+    return fail(LS_ERR_INVALID_ARG, "%s: cu_seqlens must start at 0 and end at total_tokens", who);
+  int max_len = 0;
+  for (int b = 0; b < batch; ++b) {
+    int len = cu_host[b + 1] - cu_host[b];
+    if (len > max_len) max_len = len;
+    if (len < 1) return fail(LS_ERR_INVALID_ARG, "%s: sequence %d has length %d", who, b, len);
+    if (len > (int)s->cfg.max_seq)
+      return fail(LS_ERR_KV_OVERFLOW, "%s: sequence %d has %d tokens, max_seq is %u", who, b, len, s->cfg.max_seq);
+  }
+  if (max_len_out) *max_len_out = max_len;
+  return LS_OK;
+}
+
+ls_status check_decode(const char* who, const ls_stage* s, int batch, int max_ctx) {
+  ls_status rc = check_state(who, s, batch);
+  if (rc != LS_OK) return rc;
+  if (max_ctx < 0) return fail(LS_ERR_INVALID_ARG, "%s: max_ctx %d is negative", who, max_ctx);
+  if (max_ctx + 1 > (int)s->cfg.max_seq)
+    return fail(LS_ERR_KV_OVERFLOW, "%s: context %d + 1 exceeds max_seq %u", who, max_ctx, s->cfg.max_seq);
+  return LS_OK;
+}
+
+ls_status check_pointers(const char* who, const ls_stage* s, const void* in, const ls_kv* kv, const void* out,
+                         const float* logits_out) {
+  if (!s || !in || !kv || !out) return fail(LS_ERR_INVALID_ARG, "%s: NULL argument", who);
+  if (!kv->k || !kv->v || !kv->seq_lens) return fail(LS_ERR_INVALID_ARG, "%s: NULL pointer inside ls_kv", who);
+  if (logits_out && !s->last) return fail(LS_ERR_INVALID_ARG, "%s: logits_out given but the stage has no LM head", who);
+  return LS_OK;
+}
+
+ls::GemmScratch workspace_scratch(const ls_stage* s) {
+  ls::GemmScratch g;
+  g.splitk = s->w.splitk_bytes ? (float*)(s->ws + s->w.splitk) : nullptr;
+  g.bytes = s->w.splitk_bytes;
+  return g;
 }
 
 }  // namespace
 
 extern "C" {
 
+ls_status ls_stage_check_prefill(const ls_stage* s, const int32_t* cu_host, int batch, int total_tokens) {
+  return check_prefill("ls_stage_check_prefill", s, cu_host, batch, total_tokens, nullptr);
+}
+
+ls_status ls_stage_check_decode(const ls_stage* s, int batch, int max_ctx) {
+  return check_decode("ls_stage_check_decode", s, batch, max_ctx);
+}
+
 ls_status ls_stage_prefill(ls_stage* s, const void* in, const int32_t* cu_dev, const int32_t* cu_host, int batch,
                            int total_tokens, const ls_kv* kv, void* out, float* logits_out, void* hip_stream) {
-  ls_status rc = common_checks("ls_stage_prefill", s, in, batch, kv, out, logits_out);
+  ls_status rc = check_pointers("ls_stage_prefill", s, in, kv, out, logits_out);
   if (rc != LS_OK) return rc;
-  if (!cu_dev || !cu_host) return fail(LS_ERR_INVALID_ARG, "ls_stage_prefill: NULL cu_seqlens");
-  if (total_tokens < batch || total_tokens > (int)s->cfg.max_tokens)
-    return fail(LS_ERR_INVALID_ARG, "ls_stage_prefill: total_tokens %d outside [%d,%u]", total_tokens, batch, s->cfg.max_tokens);
-  if (cu_host[0] != 0 || cu_host[batch] != total_tokens)
-    return fail(LS_ERR_INVALID_ARG, "ls_stage_prefill: cu_seqlens must start at 0 and end at total_tokens");
+  if (!cu_dev) return fail(LS_ERR_INVALID_ARG, "ls_stage_prefill: NULL cu_seqlens");
   int max_len = 0;
-  for (int b = 0; b < batch; ++b) {
-    int len = cu_host[b + 1] - cu_host[b];
-    if (len > max_len) max_len = len;
-    if (len < 1) return fail(LS_ERR_INVALID_ARG, "ls_stage_prefill: sequence %d has length %d", b, len);
-    if (len > (int)s->cfg.max_seq)
-      return fail(LS_ERR_KV_OVERFLOW, "ls_stage_prefill: sequence %d has %d tokens, max_seq is %u", b, len, s->cfg.max_seq);
-  }
-  return forward(s, true, in, cu_dev, batch, total_tokens, max_len, kv, out, logits_out, (hipStream_t)hip_stream);
+  rc = check_prefill("ls_stage_prefill", s, cu_host, batch, total_tokens, &max_len);
+  if (rc != LS_OK) return rc;
+  return forward(s, true, in, cu_dev, batch, total_tokens, max_len, kv, out, logits_out, (hipStream_t)hip_stream,
+                 workspace_scratch(s));
 }
 
 ls_status ls_stage_decode(ls_stage* s, const void* in, int batch, int max_ctx, const ls_kv* kv, void* out,
                           float* logits_out, void* hip_stream) {
-  ls_status rc = common_checks("ls_stage_decode", s, in, batch, kv, out, logits_out);
+  ls_status rc = check_pointers("ls_stage_decode", s, in, kv, out, logits_out);
   if (rc != LS_OK) return rc;
-  if (max_ctx < 0) return fail(LS_ERR_INVALID_ARG, "ls_stage_decode: max_ctx %d is negative", max_ctx);
-  if (max_ctx + 1 > (int)s->cfg.max_seq)
-    return fail(LS_ERR_KV_OVERFLOW, "ls_stage_decode: context %d + 1 exceeds max_seq %u", max_ctx, s->cfg.max_seq);
-  return forward(s, false, in, nullptr, batch, batch, 1, kv, out, logits_out, (hipStream_t)hip_stream);
+  rc = check_decode("ls_stage_decode", s, batch, max_ctx);
+  if (rc != LS_OK) return rc;
+  return forward(s, false, in, nullptr, batch, batch, 1, kv, out, logits_out, (hipStream_t)hip_stream,
+                 workspace_scratch(s));
 }
 
 ls_status ls_stage_layer_times(ls_stage* s, float* copy_ms, float* compute_ms, float* copy_end_ms,
@@ -679,6 +732,26 @@ ls_status ls_stage_layer_times(ls_stage* s, float* copy_ms, float* compute_ms, f
     if (compute_ms) LS_HIP(hipEventElapsedTime(&compute_ms[i], s->comp_start[i], s->comp_end[i]));
     if (compute_end_ms) LS_HIP(hipEventElapsedTime(&compute_end_ms[i], origin, s->comp_end[i]));
   }
+  return LS_OK;
+}
+
+ls_status ls_stage_block_times(ls_stage* s, int layer, float* copy_ms, float* copy_end_ms) {
+  if (!s) return fail(LS_ERR_INVALID_ARG, "ls_stage_block_times: NULL stage");
+  const Block* b = s->find(layer);
+  if (!b) return fail(LS_ERR_BLOCK_RANGE, "ls_stage_block_times: block %d is not held by stage [%d,%d)", layer, s->lo, s->hi);
+  if (!b->timed || s->origin_block < 0)
+    return fail(LS_ERR_INVALID_ARG, "ls_stage_block_times: block %d was not copied with profiling on", layer);
+  if (copy_ms) LS_HIP(hipEventElapsedTime(copy_ms, b->copy_start, b->loaded));
+  if (copy_end_ms) LS_HIP(hipEventElapsedTime(copy_end_ms, s->blocks[s->origin_block].copy_start, b->loaded));
+  return LS_OK;
+}
+
+ls_status ls_stage_pass_times(ls_stage* s, float* before_layers_ms, float* after_layers_ms, float* total_ms) {
+  if (!s) return fail(LS_ERR_INVALID_ARG, "ls_stage_pass_times: NULL stage");
+  if (!s->compute_timed) return fail(LS_ERR_INVALID_ARG, "ls_stage_pass_times: no prefill was recorded with profiling on");
+  if (before_layers_ms) LS_HIP(hipEventElapsedTime(before_layers_ms, s->pass_start, s->comp_start[0]));
+  if (after_layers_ms) LS_HIP(hipEventElapsedTime(after_layers_ms, s->comp_end.back(), s->pass_end));
+  if (total_ms) LS_HIP(hipEventElapsedTime(total_ms, s->pass_start, s->pass_end));
   return LS_OK;
 }
 
@@ -713,6 +786,19 @@ ls_status ls_stage_probe(ls_stage* s, int op, int layer, int phase) {
   s->probe_layer = layer;
   s->probe_phase = phase;
   if (op != LS_OP_NONE) s->probe_count = 0;  // switching off keeps what was recorded readable
+  return LS_OK;
+}
+
+ls_status ls_stage_workspace_region(const ls_stage* s, int which, size_t* offset, size_t* bytes) {
+  if (!s || !offset || !bytes) return fail(LS_ERR_INVALID_ARG, "ls_stage_workspace_region: NULL argument");
+  const ls_cfg& c = s->cfg;
+  const size_t T = c.max_tokens, e = isz(&c);
+  switch (which) {
+    case LS_WS_QKV: *offset = s->w.qkv; *bytes = T * (size_t)(c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim * e; break;
+    case LS_WS_ATTN: *offset = s->w.attn; *bytes = T * (size_t)c.n_q_heads * c.head_dim * e; break;
+    case LS_WS_FFN: *offset = s->w.h; *bytes = T * (size_t)c.ffn * e; break;
+    default: return fail(LS_ERR_INVALID_ARG, "ls_stage_workspace_region: unknown region %d", which);
+  }
   return LS_OK;
 }
 

@@ -66,42 +66,55 @@ def rel_l2(got, want):
 
 # Tolerances of the benchmark definition (relative L2 over an output) ...
 TOL = {"f32": 1e-4, "bf16": 2e-2}
-# ... and their element-level companions.  An output element's error is bounded against the
-# output's own scale: |got - want| <= K_ELEM * u * rms(want), u = 2^-8 for bf16 storage (one
-# rounding of a value near rms is at most 2^-9 rms; errors of the bf16 hand-offs between kernels
-# add up over the layers roughly like a Gaussian of standard deviation rel_l2 * rms, whose largest
-# of 10^6..10^8 samples sits near 5.5 standard deviations) and 2^-20 for the fp32 path (fp32
-# accumulation against fp64).  A wholly wrong element is off by about rms, i.e. 256 u.
+# ... and their element-level companions.  u is the resolution of the stored output: 2^-8 for
+# bf16 (one rounding of a value v is at most 2^-9 |v|), 2^-20 for the fp32 path (fp32 accumulation
+# against fp64).  Two bounds per element:
+#   tail:   |got - want| <= u |want| + TAIL * rms(row of got - want): beyond the rounding of the
+#           stored value itself, no element may stick out of its own row's error level.  Errors
+#           of the bf16 hand-offs between kernels add up like a Gaussian, whose largest of
+#           10^6..10^8 samples sits near 5.5 standard deviations; rows whose error level varies
+#           across columns by 1.5x reach 8.  An isolated wrong element is caught from about a
+#           tenth of the output's scale downwards, however little it moves the L2 norms.
+#   scale:  |got - want| <= K_ELEM u rms(want): a Gaussian error at the stated tolerance itself
+#           (2e-2) peaks at 5.7 x 2e-2 x 256 u = 29 u; the largest measured anywhere is 17 u (the
+#           8-layer 7B stage).  A wholly wrong element is off by about rms(want) = 256 u.
 U_ELEM = {"f32": 2.0**-20, "bf16": 2.0**-8}
-K_ELEM = 12.0
+TAIL = 10.0
+K_ELEM = 40.0
 ROW_FACTOR = 2.0   # no single row's relative L2 error above ROW_FACTOR * TOL
 COL_FACTOR = 2.0   # no single column's error (over >= 16 rows, against rms(want)) above COL_FACTOR * TOL
 
 
-def check_close(got, want, dtype, what=""):
+def check_close(got, want, dtype, what="", tail=None):
     """Compare one output [rows, cols] with the oracle's: relative L2 over the whole output
-    (the stated tolerance), per row, per column, and the largest element error against the
-    output's scale.  Prints what it measured, then asserts."""
+    (the stated tolerance), per row, per column, and element by element.  Prints what it
+    measured, then asserts.  `tail` overrides TAIL for outputs whose element errors are not
+    sums of many terms (see the callers)."""
     got = np.asarray(got, np.float64).reshape(np.shape(want))
     want = np.asarray(want, np.float64)
     if want.ndim == 1:
         got, want = got[None, :], want[None, :]
     diff = got - want
+    u = U_ELEM[dtype]
     rms = float(np.sqrt(np.mean(want * want)))
+    row_rms = np.sqrt(np.mean(diff * diff, axis=1, keepdims=True))
+    excess = np.maximum(np.abs(diff) - u * np.abs(want), 0.0) / np.maximum(row_rms, u * rms / 16)
     m = {
         "rel_l2": float(np.linalg.norm(diff) / np.linalg.norm(want)),
         "row": float((np.linalg.norm(diff, axis=1) / np.linalg.norm(want, axis=1)).max()),
         "col": float((np.linalg.norm(diff, axis=0) / (rms * math.sqrt(want.shape[0]))).max()),
         "elem": float(np.abs(diff).max() / rms),
+        "tail": float(excess.max()),
     }
-    print("parity %-58s rows %5d  rel-L2 %.2e  worst row %.2e  worst column %.2e  max|err|/rms %.2e (%.1f u)"
-          % (str(what)[:58], want.shape[0], m["rel_l2"], m["row"], m["col"], m["elem"], m["elem"] / U_ELEM[dtype]))
+    print("parity %-56s rows %5d  rel-L2 %.2e  worst row %.2e  column %.2e  element %.2e rms (%.1f u), %.1f sigma of its row"
+          % (str(what)[:56], want.shape[0], m["rel_l2"], m["row"], m["col"], m["elem"], m["elem"] / u, m["tail"]))
     assert np.isfinite(got).all(), what
     assert m["rel_l2"] <= TOL[dtype], (what, m)
     assert m["row"] <= ROW_FACTOR * TOL[dtype], (what, m, int((np.linalg.norm(diff, axis=1) / np.linalg.norm(want, axis=1)).argmax()))
     if want.shape[0] >= 16:
         assert m["col"] <= COL_FACTOR * TOL[dtype], (what, m, int(np.linalg.norm(diff, axis=0).argmax()))
-    assert m["elem"] <= K_ELEM * U_ELEM[dtype], (what, m, np.unravel_index(np.abs(diff).argmax(), diff.shape))
+    assert m["tail"] <= (TAIL if tail is None else tail), (what, m, np.unravel_index(excess.argmax(), diff.shape))
+    assert m["elem"] <= K_ELEM * u, (what, m, np.unravel_index(np.abs(diff).argmax(), diff.shape))
     return m
 
 

@@ -10,7 +10,7 @@ import numpy as np
 import pytest
 
 import synth
-from helpers import greedy_agreement, make_gpu, make_oracle, rel_l2, to_dev, to_host
+from helpers import check_close, greedy_agreement, make_gpu, make_oracle, rel_l2, to_dev, to_host
 
 pytestmark = pytest.mark.gpu
 
@@ -72,7 +72,7 @@ def test_recomputed_cache_equals_the_pipeline_built_cache_and_generation_continu
     # both agree with the oracle run over the same token sequence
     ora = make_oracle(SHAPE, SEED, 0, L, B, max_s)
     nt_o, lg_o = ora.prefill(np.concatenate(seqs), new_len)
-    assert rel_l2(to_host(lg_re), lg_o) <= 2e-2
+    check_close(to_host(lg_re), lg_o, "bf16", "logits after the cache was recomputed")
     _, adj, n = greedy_agreement(nxt.cpu().numpy(), to_host(lg_re), nt_o, lg_o)
     assert adj == n
     _, adj, n = greedy_agreement(tok_h[gen], to_host(lg_re), nt_o, lg_o)
@@ -86,7 +86,7 @@ def test_recomputed_cache_equals_the_pipeline_built_cache_and_generation_continu
         nt_o, lg_o = ora.decode(feed.cpu().numpy().astype(np.int32))
         torch.cuda.synchronize()
         assert rel_l2(to_host(w_lg), to_host(p_lg)) <= 2e-2
-        assert rel_l2(to_host(w_lg), lg_o) <= 2e-2
+        check_close(to_host(w_lg), lg_o, "bf16", "continued generation")
         _, adj, n = greedy_agreement(w_tok.cpu().numpy(), to_host(w_lg), nt_o, lg_o)
         assert adj == n
         feed = to_dev(SHAPE, nt_o.astype(np.int32))  # teacher forcing for all three

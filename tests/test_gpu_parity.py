@@ -9,11 +9,10 @@ import numpy as np
 import pytest
 
 import synth
-from helpers import greedy_agreement, make_gpu, make_oracle, packed_blocks, rel_l2, to_dev, to_host
+from helpers import (TOL, check_close, check_delta, greedy_agreement, make_gpu, make_oracle, packed_blocks, rel_l2,
+                     to_dev, to_host)
 
 pytestmark = pytest.mark.gpu
-
-TOL = {"f32": 1e-4, "bf16": 2e-2}
 
 # a small bf16 decoder with grouped-query attention, several tiles wide plus ragged tails
 MINI_BF16 = synth.StageShape("bf16", 3, 512, 8, 2, 64, 1408, 1000)
@@ -30,14 +29,15 @@ def run_full_model(shape, seed, lengths, steps):
     tok = synth.token_ids(seed + 1, sum(lengths), shape.vocab)
     nt_o, lg_o = ora.prefill(tok, lengths)
     nt_g, lg_g = gpu.prefill(to_dev(shape, tok), lengths, want_logits=True)
-    errs = [rel_l2(to_host(lg_g), lg_o)]
-    agree = [greedy_agreement(nt_g.cpu().numpy(), to_host(lg_g), nt_o, lg_o)]
+    what = "%s d%d V%d B%d" % (shape.dtype, shape.hidden, shape.vocab, B)
+    errs = [check_close(to_host(lg_g), lg_o, shape.dtype, what + " prompt logits")["rel_l2"]]
+    agree = [greedy_agreement(nt_g.cpu().numpy(), to_host(lg_g), nt_o, lg_o, shape.dtype)]
     for t in range(steps):
         feed = nt_o.copy()  # teacher forcing: both sides consume the oracle's tokens
         nt_o, lg_o = ora.decode(feed)
         nt_g, lg_g = gpu.decode(to_dev(shape, feed), B, S + t, want_logits=True)
-        errs.append(rel_l2(to_host(lg_g), lg_o))
-        agree.append(greedy_agreement(nt_g.cpu().numpy(), to_host(lg_g), nt_o, lg_o))
+        errs.append(check_close(to_host(lg_g), lg_o, shape.dtype, what + " step %d logits" % t)["rel_l2"])
+        agree.append(greedy_agreement(nt_g.cpu().numpy(), to_host(lg_g), nt_o, lg_o, shape.dtype))
     assert gpu.seq_lens.cpu().numpy()[:B].tolist() == [n + steps for n in lengths]
     gpu.close()
     return errs, agree
@@ -77,15 +77,17 @@ def test_middle_stage_hidden_parity_and_decode(shape, lengths):
     x = synth.hidden_states(shape, seed + 1, sum(lengths))
     want = ora.prefill(x, lengths)
     got = to_host(gpu.prefill(to_dev(shape, x), lengths))
-    assert rel_l2(got, want) <= TOL[shape.dtype]
-    # per-row check too: no single row may be far off (catches a bad ragged tail)
-    row_err = np.linalg.norm(got - want, axis=1) / np.linalg.norm(want, axis=1)
-    assert row_err.max() <= 3 * TOL[shape.dtype], row_err.max()
+    what = "%s d%d Hq%d/Hkv%d hd%d" % (shape.dtype, shape.hidden, shape.n_q_heads, shape.n_kv_heads, shape.head_dim)
+    # whole output, every row (a bad ragged tail), every column (a bad tile edge), every element
+    check_close(got, want, shape.dtype, what + " prompt")
+    from oracle.stage_oracle import decode_values
+    check_delta(got, want, decode_values(x), shape.dtype, what + " prompt")
     for t in range(steps):
         xs = synth.hidden_states(shape, seed + 2 + t, B)
         want = ora.decode(xs)
         got = to_host(gpu.decode(to_dev(shape, xs), B, S + t))
-        assert rel_l2(got, want) <= TOL[shape.dtype], t
+        check_close(got, want, shape.dtype, what + " step %d" % t)
+        check_delta(got, want, decode_values(xs), shape.dtype, what + " step %d" % t)
     gpu.close()
 
 
@@ -105,10 +107,14 @@ def test_split_stages_equal_whole_stage():
         b = make_gpu(shape, seed, k, 3, B, S + 2, sum(lengths))
         got = b.prefill(a.prefill(to_dev(shape, x), lengths), lengths)
         got_d = b.decode(a.decode(to_dev(shape, xs), B, S), B, S)
-        # the hand-off rounds the residual stream to bf16 once: equal within that rounding
-        assert rel_l2(to_host(got), to_host(ref)) <= 2.0**-7
-        assert rel_l2(to_host(got_d), to_host(ref_d)) <= 2.0**-7
-        assert rel_l2(to_host(got), want) <= TOL["bf16"]
+        # Inside a stage the residual stream is fp32; the hand-off rounds it to bf16 once (at
+        # most 2^-9 per element, about 0.3 * 2^-8 in relative L2), and where that moves the
+        # second stage's result across a rounding boundary of its own bf16 output the two
+        # outputs differ by one more such step: at most 2^-8 in relative L2, not bitwise.
+        e_p, e_d = rel_l2(to_host(got), to_host(ref)), rel_l2(to_host(got_d), to_host(ref_d))
+        print("split at %d: two stages vs one, rel-L2 %.2e (prompt) %.2e (step); 2^-8 = %.2e" % (k, e_p, e_d, 2.0**-8))
+        assert e_p <= 2.0**-8 and e_d <= 2.0**-8
+        check_close(to_host(got), want, "bf16", "two stages split at %d vs oracle" % k)
         a.close(); b.close()
     whole.close()
 

@@ -7,7 +7,7 @@ import numpy as np
 import pytest
 
 import synth
-from helpers import greedy_agreement, make_gpu, make_oracle, rel_l2, to_dev, to_host
+from helpers import check_close, greedy_agreement, make_gpu, make_oracle, packed_blocks, rel_l2, to_dev, to_host
 
 pytestmark = pytest.mark.gpu
 
@@ -91,7 +91,7 @@ def test_pipelined_microbatches_equal_serial_runs_and_the_oracle(cuts):
         for t in range(steps + 1):
             mine = got[m][t].cpu().numpy()
             lg_g = to_host(logits[t][m])
-            assert rel_l2(lg_g, lg) <= 2e-2, (m, t)
+            check_close(lg_g, lg, "bf16", "pipelined micro-batch %d call %d" % (m, t))
             _, a_, n_ = greedy_agreement(mine, lg_g, nt, lg)
             adj += a_
             n += n_
@@ -116,3 +116,52 @@ def test_pipeline_rejects_stages_that_do_not_follow_each_other():
     with pytest.raises(LsError):
         Pipeline([a, other])
     a.close(); c.close(); other.close()
+
+
+def test_a_failing_pipeline_pass_enqueues_nothing_in_any_stage():
+    """Errors that only a later stage or a later micro-batch shows (a block never enqueued for
+    load, a malformed cu_seqlens) are found before the first enqueue: no stage's cache
+    lengths move."""
+    import ctypes as C
+    import torch
+    from paper_2502_09922_amd import LsError, MicroBatch, Pipeline, binding as b
+
+    a = make_gpu(SHAPE, SEED, 0, 2, 2, 32, 32)
+    c = make_gpu(SHAPE, SEED, 2, 4, 2, 32, 32, load=False)  # holds layers 2, 3 and the head: none loaded
+    pipe = Pipeline([a, c])
+    mbs = [MicroBatch(pipe, 32) for _ in range(2)]
+    for mb in mbs:
+        for _, _, sl in mb.caches:
+            sl.fill_(-3)
+    x = [to_dev(SHAPE, synth.token_ids(SEED + m, 12, SHAPE.vocab)) for m in range(2)]
+    with pytest.raises(LsError) as e:
+        pipe.run(0, mbs, x, lengths=[[5, 7], [12]])
+    assert e.value.status == b.LS_ERR_NOT_LOADED
+    blocks = packed_blocks(c, SEED)
+    for l, buf in blocks.items():
+        c.load_block(l, c.stage_host_block(l, buf))
+    # micro-batch 1 declares 12 rows but its cu_seqlens ends at 11
+    arr = (b.ls_microbatch * 2)()
+    keep = []
+    for m, lens in enumerate([[5, 7], [11]]):
+        cu = np.zeros(len(lens) + 1, np.int32)
+        cu[1:] = np.cumsum(lens)
+        cu_dev = torch.from_numpy(cu).cuda()
+        out = torch.empty(len(lens), dtype=torch.int32, device="cuda")
+        keep += [cu, cu_dev, out]
+        arr[m].in_ = x[m].data_ptr()
+        arr[m].cu_seqlens_dev = cu_dev.data_ptr()
+        arr[m].cu_seqlens_host = cu.ctypes.data_as(C.POINTER(C.c_int32))
+        arr[m].batch, arr[m].total_tokens = len(lens), 12
+        arr[m].kv, arr[m].handoff, arr[m].out = mbs[m].kv, mbs[m].handoff, out.data_ptr()
+    torch.cuda.synchronize()
+    assert b.ls_pipeline_run(pipe.handle, 0, arr, 2, pipe._stream_ptrs) == b.LS_ERR_INVALID_ARG
+    torch.cuda.synchronize()
+    for mb in mbs:
+        for _, _, sl in mb.caches:
+            assert (sl.cpu() == -3).all()
+    # the same pipeline still runs a well-formed pass
+    pipe.run(0, mbs, x, lengths=[[5, 7], [12]])
+    torch.cuda.synchronize()
+    assert mbs[0].caches[1][2].cpu().tolist() == [5, 7] and mbs[1].caches[0][2].cpu().tolist()[:1] == [12]
+    pipe.close(); a.close(); c.close()

@@ -1,13 +1,15 @@
-"""Parity at the benchmark's real layer dimensions and in the launch configuration that
+"""Parity at the benchmark's real layer dimensions and in the launch configurations that
 bench.py times.
 
 The oracle cannot run a whole 7B stage on 4096 rows in test time, so:
-  * at the full bench configuration (8 layers, batch 8 x 512, then decode) the GPU runs
-    everything, and the oracle recomputes ONE sequence alone -- causal attention makes a
-    sequence's outputs independent of the other sequences in the batch, so every row of
-    that sequence (prompt pass and decode steps) is compared element by element;
-  * the 13B- and 70B-shaped layers (first / last stage pieces, GQA, LM head at V=32000)
-    run as one-layer slices on short ragged batches, compared in full.
+  * at the full launch shapes (the whole batch of the benchmark configuration) the GPU runs
+    everything, and the oracle recomputes PICKED sequences alone -- causal attention makes a
+    sequence's outputs independent of the other sequences in the batch, so every row of those
+    sequences (prompt pass and decode steps) is compared element by element;
+  * single operators (QKV projection + RoPE, cache append, attention, SwiGLU) are compared at
+    the 7B shape from the intermediate results the stage leaves in the caller's workspace;
+  * the LM head at V = 32000 and its greedy tokens run on a last-stage piece over short prompts,
+    where the oracle can afford every sequence.
 """
 from concurrent.futures import ThreadPoolExecutor
 
@@ -15,51 +17,170 @@ import numpy as np
 import pytest
 
 import synth
-from helpers import block_tensors, make_gpu, make_oracle, rel_l2, to_dev, to_host
-from oracle.stage_oracle import OracleStage
+from helpers import TOL, check_close, check_delta, greedy_agreement, make_gpu, make_oracle, to_dev, to_host
+from oracle import stage_oracle as so
+from oracle.stage_oracle import OracleStage, decode_values
 
 pytestmark = pytest.mark.gpu
-TOL = 2e-2
 
 
-def test_bench_configuration_llama7b_stage_sampled_sequence():
-    """Layers 8..15 of the 7B shape, batch 8 x 512 prompt rows, then 3 decode steps: the
-    exact launch shapes of the default bench workload.  Sequences 5 and 7 are checked against
-    the oracle run on each of them alone (the rows of sequence 7 lie in the last, partial
-    round of the gate-up GEMM's tiles); all sequences are checked for finiteness."""
-    shape, seed, lo, hi = synth.CONFIGS["llama7b"], 1234, 8, 16
-    B, S, steps, picks = 8, 512, 3, (5, 7)
+def layers_of(shape, seed, lo, hi):
     with ThreadPoolExecutor(8) as ex:
-        tensors = dict(zip(range(lo, hi), ex.map(lambda l: synth.layer_tensors(shape, seed, l), range(lo, hi))))
+        return dict(zip(range(lo, hi), ex.map(lambda l: synth.layer_tensors(shape, seed, l), range(lo, hi))))
+
+
+def gpu_stage(shape, tensors, lo, hi, B, max_seq, T):
+    import torch
     from paper_2502_09922_amd import Stage, pack_block
 
-    gpu = Stage(shape, lo, hi, B, S + 128, B * S)
+    gpu = Stage(shape, lo, hi, B, max_seq, T)
     for l in range(lo, hi):
         gpu.load_block(l, gpu.stage_host_block(l, pack_block(gpu.cfg, l, [tensors[l][n] for n in synth.TENSOR_ORDER_LAYER])))
-    x = synth.hidden_states(shape, seed + 1, B * S)
-    got = to_host(gpu.prefill(to_dev(shape, x), [S] * B))
+        torch.cuda.synchronize()  # the copy has landed:
+        gpu._pinned.pop(l)        # its pinned staging buffer can go
+    return gpu
+
+
+def oracle_on_picks(shape, tensors, lo, hi, x, lengths, picks, dec_in, steps):
+    """The picked sequences as an oracle batch of their own: (prompt outputs per pick, list of
+    per-step outputs [len(picks), d])."""
+    off = np.concatenate([[0], np.cumsum(lengths)])
+    ora = OracleStage(shape, lo, hi, len(picks), max(lengths[b] for b in picks) + steps)
+    for l in range(lo, hi):
+        ora.load_tensors(l, tensors[l])
+    xs = np.concatenate([x[off[b]:off[b + 1]] for b in picks])
+    want = ora.prefill(xs, [lengths[b] for b in picks])
+    o2 = np.concatenate([[0], np.cumsum([lengths[b] for b in picks])])
+    per_pick = [want[o2[i]:o2[i + 1]] for i in range(len(picks))]
+    dec = [ora.decode(dec_in[t][list(picks)]) for t in range(steps)]
+    return per_pick, dec
+
+
+def run_sampled(shape, tag, lo, hi, lengths, steps, picks, seed=1234):
+    """GPU: the whole batch.  Oracle: the picked sequences.  Everything of those sequences is
+    compared: relative L2, per row, per column, per element, and the stage's own delta."""
+    B, S, T = len(lengths), max(lengths), sum(lengths)
+    tensors = layers_of(shape, seed, lo, hi)
+    gpu = gpu_stage(shape, tensors, lo, hi, B, S + steps, T)
+    x = synth.hidden_states(shape, seed + 1, T)
+    got = to_host(gpu.prefill(to_dev(shape, x), lengths))
     assert np.isfinite(got).all()
     dec_in = [synth.hidden_states(shape, seed + 2 + t, B) for t in range(steps)]
     got_dec = [to_host(gpu.decode(to_dev(shape, dec_in[t]), B, S + t)) for t in range(steps)]
+    assert gpu.seq_lens.cpu().numpy()[:B].tolist() == [n + steps for n in lengths]
+    gpu.close()
+    for g in got_dec:
+        assert np.isfinite(g).all()
+    off = np.concatenate([[0], np.cumsum(lengths)])
+    want, want_dec = oracle_on_picks(shape, tensors, lo, hi, x, lengths, picks, dec_in, steps)
+    for i, b in enumerate(picks):
+        mine = got[off[b]:off[b + 1]]
+        check_close(mine, want[i], "bf16", "%s prompt, sequence %d (%d rows)" % (tag, b, lengths[b]))
+        check_delta(mine, want[i], decode_values(x[off[b]:off[b + 1]]), "bf16", "%s prompt, sequence %d" % (tag, b))
+    # decode: the picked sequences' rows of every step, stacked (rows = steps x picks)
+    g = np.concatenate([got_dec[t][list(picks)] for t in range(steps)])
+    w = np.concatenate(want_dec)
+    check_close(g, w, "bf16", "%s %d decode steps, sequences %s" % (tag, steps, list(picks)))
+    xin = np.concatenate([decode_values(dec_in[t][list(picks)]) for t in range(steps)])
+    check_delta(g, w, xin, "bf16", "%s %d decode steps" % (tag, steps))
+
+
+def test_llama7b_stage_full_launch_shape_through_all_128_decode_steps():
+    """Benchmark configuration 2 as bench.py launches it: layers 8..15, batch 8 x 512 prompt
+    rows, then all 128 decode steps (contexts 512..639).  Sequences 5 and 7 are checked against
+    the oracle (the rows of sequence 7 lie in the last, partial round of the gate-up GEMM's tiles)."""
+    run_sampled(synth.CONFIGS["llama7b"], "7B stage 8x512", 8, 16, [512] * 8, 128, (5, 7))
+
+
+def test_llama13b_two_layers_full_batch_contexts_across_tile_edges():
+    """Configuration 3's launch shapes: 32 x 1024 prompt rows through two 13B-shaped layers, then
+    8 decode steps of 32 rows: contexts 1024..1031 start a new 32- and 64-key tile at the first step."""
+    run_sampled(synth.CONFIGS["llama13b"].with_(vocab=0), "13B 32x1024", 16, 18, [1024] * 32, 8, (0, 21))
+
+
+def test_llama70b_two_layers_full_ragged_batch():
+    """Configuration 4's launch shapes: 64 ragged prompts of 128..2048 rows through two 70B-shaped
+    grouped-query layers, then 8 decode steps of 64 rows; the longest sequence, one that ends
+    just under a 64-key tile edge and one in the middle are checked."""
+    import bench
+
+    lengths = bench.prompt_lengths(synth, 64, (128, 2048))
+    longest = int(np.argmax(lengths))
+    # the sequence whose length is closest below a multiple of 64 (its decode steps cross the edge)
+    edge = int(np.argmin([(-n) % 64 if (-n) % 64 else 64 for n in lengths]))
+    picks = tuple(dict.fromkeys((3, edge, longest)))
+    run_sampled(synth.CONFIGS["llama70b"].with_(vocab=0), "70B 64 ragged", 40, 42, lengths, 8, picks)
+
+
+def test_single_operators_at_the_7b_shape_from_the_workspace():
+    """One 7B-shaped layer on 8 x 512 prompt rows; the intermediate results the stage leaves in
+    the workspace and the cache are compared operator by operator for one sequence: rotated
+    queries, cached keys and values, attention output, SwiGLU output."""
+    from paper_2502_09922_amd import binding as b
+
+    shape, seed, layer, B, S, pick = synth.CONFIGS["llama7b"].with_(vocab=0), 1234, 9, 8, 512, 6
+    tensors = layers_of(shape, seed, layer, layer + 1)
+    gpu = gpu_stage(shape, tensors, layer, layer + 1, B, S + 1, B * S)
+    x = synth.hidden_states(shape, seed + 1, B * S)
+    gpu.prefill(to_dev(shape, x), [S] * B)
+    rows = slice(pick * S, (pick + 1) * S)
+    hq, hkv, hd, d = shape.n_q_heads, shape.n_kv_heads, shape.head_dim, shape.hidden
+    q_g = to_host(gpu.workspace_region(b.LS_WS_QKV, B * S)[rows, : hq * hd])
+    attn_g = to_host(gpu.workspace_region(b.LS_WS_ATTN, B * S)[rows])
+    ffn_g = to_host(gpu.workspace_region(b.LS_WS_FFN, B * S)[rows])
+    kc = gpu.k.view(gpu.tdtype).view(1, B, hkv, S + 1, hd)
+    vc = gpu.v.view(gpu.tdtype).view(1, B, hkv, S + 1, hd)
+    k_g, v_g = to_host(kc[0, pick, :, :S]), to_host(vc[0, pick, :, :S])
     gpu.close()
 
-    for pick in picks:
-        ora = OracleStage(shape, lo, hi, 1, S + steps)
-        for l in range(lo, hi):
-            ora.load_tensors(l, tensors[l])
-        want = ora.prefill(x[pick * S : (pick + 1) * S], [S])
-        mine = got[pick * S : (pick + 1) * S]
-        assert rel_l2(mine, want) <= TOL, pick
-        row_err = np.linalg.norm(mine - want, axis=1) / np.linalg.norm(want, axis=1)
-        assert row_err.max() <= 2 * TOL, (pick, row_err.argmax(), row_err.max())
-        for t in range(steps):
-            want_t = ora.decode(dec_in[t][pick : pick + 1])
-            assert rel_l2(got_dec[t][pick : pick + 1], want_t) <= TOL, (pick, t)
-            assert np.isfinite(got_dec[t]).all()
+    w = {n: decode_values(t) for n, t in tensors[layer].items()}
+    xs = decode_values(x[rows])
+    pos = np.arange(S)
+    qkv = so.rmsnorm(xs, w["attn_norm"], shape.rms_eps) @ w["wqkv"].T
+    q = so.rope(qkv[:, : hq * hd].reshape(S, hq, hd), pos, shape.rope_base)
+    k = so.rope(qkv[:, hq * hd : (hq + hkv) * hd].reshape(S, hkv, hd), pos, shape.rope_base)
+    v = qkv[:, (hq + hkv) * hd :].reshape(S, hkv, hd)
+    check_close(q_g, q.reshape(S, -1), "bf16", "7B layer: rotated queries")
+    check_close(k_g.transpose(1, 0, 2).reshape(S, -1), k.reshape(S, -1), "bf16", "7B layer: cached keys")
+    check_close(v_g.transpose(1, 0, 2).reshape(S, -1), v.reshape(S, -1), "bf16", "7B layer: cached values")
+    o = so.attention_rows(q, k.transpose(1, 0, 2), v.transpose(1, 0, 2), pos)
+    # Attention rows over one or a few keys and the product silu(gate) * up are not sums of many
+    # terms: an element's error is a product of two roughly Gaussian factors (the value's own
+    # size times the relative error of its factors), whose largest of 5.6 million samples lies
+    # near ln(5.6e6) = 15.5 standard deviations, not 5.5; the tail bound is widened to 20 here.
+    check_close(attn_g, o.reshape(S, -1), "bf16", "7B layer: attention output", tail=20.0)
+    x1 = xs + o.reshape(S, -1) @ w["wo"].T
+    gu = so.rmsnorm(x1, w["ffn_norm"], shape.rms_eps) @ w["wgu"].T
+    check_close(ffn_g, so.silu(gu[:, : shape.ffn]) * gu[:, shape.ffn :], "bf16", "7B layer: SwiGLU output", tail=20.0)
+
+
+def test_greedy_tokens_and_logits_at_vocab_32000():
+    """Last-stage piece of the 13B shape (two layers, final norm, LM head, V = 32000) on 32
+    ragged prompts of 33..96 tokens and 8 teacher-forced decode steps: 288 greedy positions,
+    every one against the oracle."""
+    shape, seed, lo, hi, steps = synth.CONFIGS["llama13b"], 77, 38, 40, 8
+    lengths = [int(n) for n in synth.ragged_lengths(seed, 32, 33, 96)]
+    B, S, T = len(lengths), max(lengths), sum(lengths)
+    gpu = make_gpu(shape, seed, lo, hi, B, S + steps, T)
+    ora = make_oracle(shape, seed, lo, hi, B, S + steps)
+    x = synth.hidden_states(shape, seed + 1, T)
+    nt_o, lg_o = ora.prefill(x, lengths)
+    nt_g, lg_g = gpu.prefill(to_dev(shape, x), lengths, want_logits=True)
+    check_close(to_host(lg_g), lg_o, "bf16", "13B head V=32000 prompt logits")
+    raw, adj, n = greedy_agreement(nt_g.cpu().numpy(), to_host(lg_g), nt_o, lg_o)
+    for t in range(steps):
+        xs = synth.hidden_states(shape, seed + 2 + t, B)
+        nt_o, lg_o = ora.decode(xs)
+        nt_g, lg_g = gpu.decode(to_dev(shape, xs), B, S + t, want_logits=True)
+        check_close(to_host(lg_g), lg_o, "bf16", "13B head V=32000 step %d logits" % t)
+        r, a, c = greedy_agreement(nt_g.cpu().numpy(), to_host(lg_g), nt_o, lg_o)
+        raw, adj, n = raw + r, adj + a, n + c
+    gpu.close()
+    print("greedy at V=32000: %d of %d equal, %d with declared ties" % (raw, n, adj))
+    assert n == 32 * (steps + 1) and adj >= 0.99 * n and raw >= 0.97 * n, (raw, adj, n)
 
 
 @pytest.mark.parametrize("name,lo,hi,lengths,steps", [
-    ("llama13b", 39, 40, [70, 5, 33], 2),     # last stage piece: layer + final norm + LM head at V=32000
     ("llama13b", 0, 1, [64, 9], 2),           # first stage piece: embedding gather + layer
     ("llama70b", 40, 41, [130, 40, 7, 77], 3),  # grouped-query attention, 64 q heads on 8 kv heads
 ])
@@ -68,31 +189,11 @@ def test_one_layer_slices_at_real_dimensions(name, lo, hi, lengths, steps):
     B, S, T = len(lengths), max(lengths), sum(lengths)
     gpu = make_gpu(shape, seed, lo, hi, B, S + steps, T)
     ora = make_oracle(shape, seed, lo, hi, B, S + steps)
-    if gpu.first:
-        x = synth.token_ids(seed + 1, T, shape.vocab)
-    else:
-        x = synth.hidden_states(shape, seed + 1, T)
-    want = ora.prefill(x, lengths)
-    if gpu.last:
-        tok, lg = gpu.prefill(to_dev(shape, x), lengths, want_logits=True)
-        assert rel_l2(to_host(lg), want[1]) <= TOL
-        err = np.abs(to_host(lg) - want[1]).max()
-        for b in range(B):  # greedy token agrees unless the oracle's top two are a declared tie
-            top2 = np.sort(want[1][b])[-2:]
-            assert int(tok[b]) == int(want[0][b]) or top2[1] - top2[0] < 4 * err
-    else:
-        assert rel_l2(to_host(gpu.prefill(to_dev(shape, x), lengths)), want) <= TOL
+    x = synth.token_ids(seed + 1, T, shape.vocab) if gpu.first else synth.hidden_states(shape, seed + 1, T)
+    check_close(to_host(gpu.prefill(to_dev(shape, x), lengths)), ora.prefill(x, lengths), "bf16", "%s layer %d prompt" % (name, lo))
     for t in range(steps):
-        if gpu.first:
-            xs = synth.token_ids(seed + 2 + t, B, shape.vocab)
-        else:
-            xs = synth.hidden_states(shape, seed + 2 + t, B)
-        want = ora.decode(xs)
-        if gpu.last:
-            _, lg = gpu.decode(to_dev(shape, xs), B, S + t, want_logits=True)
-            assert rel_l2(to_host(lg), want[1]) <= TOL
-        else:
-            assert rel_l2(to_host(gpu.decode(to_dev(shape, xs), B, S + t)), want) <= TOL
+        xs = synth.token_ids(seed + 2 + t, B, shape.vocab) if gpu.first else synth.hidden_states(shape, seed + 2 + t, B)
+        check_close(to_host(gpu.decode(to_dev(shape, xs), B, S + t)), ora.decode(xs), "bf16", "%s layer %d step %d" % (name, lo, t))
     gpu.close()
 
 
@@ -106,55 +207,123 @@ def test_decode_with_many_sequences(batch):
     gpu = make_gpu(shape, seed, 0, 2, batch, S + steps, T)
     ora = make_oracle(shape, seed, 0, 2, batch, S + steps)
     x = synth.hidden_states(shape, seed + 1, T)
-    assert rel_l2(to_host(gpu.prefill(to_dev(shape, x), lengths)), ora.prefill(x, lengths)) <= TOL
+    check_close(to_host(gpu.prefill(to_dev(shape, x), lengths)), ora.prefill(x, lengths), "bf16", "B%d prompt" % batch)
     for t in range(steps):
         xs = synth.hidden_states(shape, seed + 2 + t, batch)
         got, want = to_host(gpu.decode(to_dev(shape, xs), batch, S + t)), ora.decode(xs)
-        assert rel_l2(got, want) <= TOL
-        row_err = np.linalg.norm(got - want, axis=1) / np.linalg.norm(want, axis=1)
-        assert row_err.max() <= 3 * TOL
+        check_close(got, want, "bf16", "B%d step %d" % (batch, t))
+        check_delta(got, want, decode_values(xs), "bf16", "B%d step %d" % (batch, t))
     gpu.close()
 
 
-@pytest.mark.parametrize("name,layer,batch,prompt,picks", [
-    # bench slices of the larger configurations, one layer of each at the full batch: the
-    # launch shapes bench.py times (many-row prompt GEMMs, decode with 32 / 64 rows, ragged
-    # contexts up to 2048 keys for the grouped-query decode attention)
-    ("llama13b", 16, 32, 1024, (0, 21)),
-    ("llama70b", 40, 64, (128, 2048), (3, "longest")),
-])
-def test_bench_slices_of_the_larger_configurations_sampled_sequences(name, layer, batch, prompt, picks):
-    """The GPU runs the whole batch; the oracle recomputes the picked sequences alone
-    (a sequence's rows do not depend on the other sequences of the batch) for the prompt
-    pass and two decode steps."""
-    import bench
-
-    shape, seed, steps = synth.CONFIGS[name].with_(vocab=0), 1234, 2
-    lengths = bench.prompt_lengths(synth, batch, prompt)
-    B, S, T = len(lengths), max(lengths), sum(lengths)
-    tensors = synth.layer_tensors(shape, seed, layer)
+def test_streamed_equals_preloaded_at_the_real_7b_layer_size():
+    """Two 405 MB blocks copied on a side stream while the prompt pass of 8 x 512 rows runs:
+    bit-identical to the same stage with both blocks resident before the call, and no NaN from
+    the poisoned slab (no kernel read a block before its gate)."""
+    import torch
     from paper_2502_09922_amd import Stage, pack_block
 
-    gpu = Stage(shape, layer, layer + 1, B, S + steps, T)
-    gpu.load_block(layer, gpu.stage_host_block(layer, pack_block(gpu.cfg, layer, [tensors[n] for n in synth.TENSOR_ORDER_LAYER])))
-    x = synth.hidden_states(shape, seed + 1, T)
-    got = to_host(gpu.prefill(to_dev(shape, x), lengths))
-    assert np.isfinite(got).all()
-    dec_in = [synth.hidden_states(shape, seed + 2 + t, B) for t in range(steps)]
-    got_dec = [to_host(gpu.decode(to_dev(shape, dec_in[t]), B, S + t)) for t in range(steps)]
-    assert gpu.seq_lens.cpu().numpy()[:B].tolist() == [n + steps for n in lengths]
+    shape, seed, lo, hi, B, S = synth.CONFIGS["llama7b"].with_(vocab=0), 1234, 8, 10, 8, 512
+    tensors = layers_of(shape, seed, lo, hi)
+    st = Stage(shape, lo, hi, B, S + 1, B * S)
+    hosts = {l: st.stage_host_block(l, pack_block(st.cfg, l, [tensors[l][n] for n in synth.TENSOR_ORDER_LAYER])) for l in range(lo, hi)}
+    x = to_dev(shape, synth.hidden_states(shape, seed + 1, B * S))
+    for l in range(lo, hi):
+        st.load_block(l, hosts[l])
+    torch.cuda.synchronize()
+    ref = st.prefill(x, [S] * B).clone()
+    ref_k = st.k.clone()
+    torch.cuda.synchronize()
+    for order in ([lo, lo + 1], [lo + 1, lo]):
+        st.reset_blocks()
+        st.slab.view(torch.int16).fill_(0x7FC0)  # bf16 NaN everywhere
+        st.k.zero_()
+        copy_stream = torch.cuda.Stream()
+        torch.cuda.synchronize()
+        for l in order:
+            st.load_block(l, hosts[l], stream=copy_stream)
+        got = st.prefill(x, [S] * B)
+        torch.cuda.synchronize()
+        assert not torch.isnan(got).any()
+        assert torch.equal(got, ref) and torch.equal(st.k, ref_k), order
+    st.close()
+
+
+def test_llama13b_whole_model_at_full_depth():
+    """Configuration 3 at its full depth: embedding, all 40 layers, final norm and LM head at
+    V = 32000 as ONE stage, on four short ragged prompts.
+
+    The oracle walks the model one layer at a time (a stage per layer; in the oracle splitting
+    a span is exact), so that only one layer's float64 weights are in host memory at once.
+      (1) Every layer of the 40, on its own: a one-layer GPU stage is fed the oracle's input of
+          that layer and must give the oracle's output of that layer within the tolerance.
+      (2) End to end, the decoder of this weight recipe amplifies a relative perturbation from
+          layer to layer, so over 40 layers a 16-bit pipeline drifts from the float64 result by
+          more than any single layer's error.  The drift is printed; the logits must match the
+          oracle's diagnostic mode, which rounds to bfloat16 where such a pipeline stores its
+          activations and drifts the same way, within the tolerance; the greedy tokens are
+          compared with the float64 oracle under the tie rule."""
+    import torch
+    from paper_2502_09922_amd import Stage, pack_block
+
+    shape, seed = synth.CONFIGS["llama13b"], 1234
+    mid = shape.with_(vocab=0)
+    L = shape.n_layers_total
+    lengths = [96, 33, 64, 70]
+    B, S, T = len(lengths), max(lengths), sum(lengths)
+    tok = synth.token_ids(seed + 1, T, shape.vocab)
+    gpu = Stage(shape, 0, L, B, S + 1, T)
+    single = Stage(mid, 5, 6, B, S + 1, T)  # re-used for every layer: a block does not carry its index
+    worst = 0.0
+    with ThreadPoolExecutor(4) as ex:
+        pending = [ex.submit(synth.layer_tensors, shape, seed, l) for l in range(min(4, L))]
+        emb = synth.embed_tensors(shape, seed)
+        gpu.load_block(-1, gpu.stage_host_block(-1, pack_block(gpu.cfg, -1, [emb["embed"]])))
+        x = decode_values(emb["embed"])[tok.astype(np.int64)]  # float64 trajectory
+        z = x.copy()                                            # trajectory of the diagnostic mode
+        for l in range(L):
+            t = pending[l].result()
+            pending[l] = None
+            if l + 4 < L:
+                pending.append(ex.submit(synth.layer_tensors, shape, seed, l + 4))
+            host = gpu.stage_host_block(l, pack_block(gpu.cfg, l, [t[n] for n in synth.TENSOR_ORDER_LAYER]))
+            gpu.load_block(l, host)
+            single.reset_blocks()
+            single.load_block(5, host)
+            got = to_host(single.prefill(to_dev(mid, synth.bf16_bits_from_f32(x.astype(np.float32))), lengths))
+            one = OracleStage(mid, l, l + 1, B, S)
+            one.load_tensors(l, t)
+            x = one.prefill(x, lengths)
+            worst = max(worst, check_close(got, x, "bf16", "13B layer %d alone, fed the oracle's input" % l)["rel_l2"])
+            emu = OracleStage(mid, l, l + 1, B, S, bf16_handoffs=True)
+            emu.round_output = False  # inside one stage the residual stream is not stored in 16 bits
+            emu.w = one.w
+            z = emu.prefill(z, lengths)
+            torch.cuda.synchronize()
+            gpu._pinned.pop(l)
+            del one, emu, t, host
+    single.close()
+    head = synth.head_tensors(shape, seed)
+    gpu.load_block(L, gpu.stage_host_block(L, pack_block(gpu.cfg, L, [head[n] for n in synth.TENSOR_ORDER_HEAD])))
+    last = np.cumsum(lengths) - 1
+    g, W = decode_values(head["final_norm"]), decode_values(head["lm_head"])
+    lg_o = so.head_logits(x[last], g, W, shape.rms_eps)
+    lg_z = so.round_bf16(so.rmsnorm(z[last], g, shape.rms_eps)) @ W.T
+    nt_o = so.greedy(lg_o)
+    nt_g, lg_g = gpu.prefill(to_dev(shape, tok), lengths, want_logits=True)
+    torch.cuda.synchronize()
     gpu.close()
-    off = np.concatenate([[0], np.cumsum(lengths)])
-    for pick in picks:
-        b = int(np.argmax(lengths)) if pick == "longest" else pick
-        ora = OracleStage(shape, layer, layer + 1, 1, lengths[b] + steps)
-        ora.load_tensors(layer, tensors)
-        want = ora.prefill(x[off[b]:off[b + 1]], [lengths[b]])
-        mine = got[off[b]:off[b + 1]]
-        assert rel_l2(mine, want) <= TOL, (b, rel_l2(mine, want))
-        row_err = np.linalg.norm(mine - want, axis=1) / np.linalg.norm(want, axis=1)
-        assert row_err.max() <= 2 * TOL, (b, row_err.argmax(), row_err.max())
-        for t in range(steps):
-            want_t = ora.decode(dec_in[t][b:b + 1])
-            assert rel_l2(got_dec[t][b:b + 1], want_t) <= TOL, (b, t)
-            assert np.isfinite(got_dec[t]).all()
+    lg_g = to_host(lg_g)
+    from helpers import rel_l2
+    e_gpu, e_emu, e_between = rel_l2(lg_g, lg_o), rel_l2(lg_z, lg_o), rel_l2(lg_g, lg_z)
+    raw, adj, n = greedy_agreement(nt_g.cpu().numpy(), lg_g, nt_o, lg_o)
+    print("13B whole model, 40 layers: worst single layer %.2e; logits end to end against float64 %.2e, diagnostic mode "
+          "against float64 %.2e, GPU against the diagnostic mode %.2e; greedy %d of %d equal, %d with declared ties"
+          % (worst, e_gpu, e_emu, e_between, raw, n, adj))
+    assert np.isfinite(lg_g).all()
+    assert worst <= TOL["bf16"]
+    # the GPU drifts no further from float64 than 16-bit storage of the activations alone does,
+    # and it lies closer to that emulation than to float64 (the two share most rounding decisions)
+    assert e_gpu <= 1.5 * e_emu, (e_gpu, e_emu)
+    assert e_between <= e_gpu, (e_between, e_gpu)
+    assert adj == n, (raw, adj, n)

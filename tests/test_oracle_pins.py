@@ -474,6 +474,24 @@ def test_embed_and_head_blocks_load_from_packed_bytes():
         a.load_block(1, hbuf[:-256])
 
 
+def test_diagnostic_bf16_mode_is_off_by_default_and_rounds_to_nearest_even():
+    f = np.array([1.0, 1.0 + 2.0**-8, 1.0 + 3 * 2.0**-8, 1.0 + 2.0**-8 + 2.0**-20, -0.3, 3.14159])
+    got = so.round_bf16(f)
+    assert got[:4].tolist() == [1.0, 1.0, 1.0 + 2.0**-6, 1.0 + 2.0**-7]  # ties go to the even pattern
+    assert got[4] == so.decode_values(synth.bf16_bits_from_f32(np.float32([-0.3])))[0]
+    assert got[5] == 3.140625
+    s = TINY.with_(vocab=0)
+    x = rnd(3, 9, s.hidden)
+    plain, again, rounded = make_stage(s), make_stage(s), make_stage(s)
+    rounded._r, rounded._rw, rounded.round_output = so.round_bf16, so.round_bf16, True
+    a, b, c = plain.prefill(x, [4, 5]), again.prefill(x, [4, 5]), rounded.prefill(x, [4, 5])
+    np.testing.assert_array_equal(a, b)
+    err = np.linalg.norm(c - a) / np.linalg.norm(a)
+    assert 1e-4 < err < 1e-2, err  # the mode perturbs at the 16-bit level, and only when asked
+    on = so.OracleStage(s, 0, 2, 4, 32, bf16_handoffs=True)
+    assert on._rw is so.round_bf16 and on.round_output and so.OracleStage(s, 0, 2, 4, 32)._rw is None
+
+
 # ----------------------------------------------------------------------------- planted mistakes
 def _run_pins():
     for fn in (
