@@ -226,6 +226,25 @@ ls_status ls_stage_decode(ls_stage* stage, const void* in, int batch, int max_ct
 ls_status ls_stage_check_prefill(const ls_stage* stage, const int32_t* cu_seqlens_host, int batch, int total_tokens);
 ls_status ls_stage_check_decode(const ls_stage* stage, int batch, int max_ctx);
 
+/*
+ * ls_stage_decode for callers that cannot allocate and want no partial results in memory
+ * they manage: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same arguments, same kernels and bit-identical results; the one difference is
+ * where the decode GEMMs that split K across workgroups (batches of 17..64 rows) stage their
+ * fp32 partial tiles: in a static device array of LS_STATIC_SCRATCH_BYTES inside the library
+ * (one copy per GPU, held until the process ends) instead of the caller's workspace.  The
+ * call allocates and frees nothing.  A step whose largest GEMM needs more than the array
+ * holds (rows x columns x K-splits x 4 bytes; 16 MiB covers 64 rows of the 7B-, 13B- and
+ * 70B-shaped layers and a 32000-entry head) is LS_ERR_OOM and enqueues nothing; the stage
+ * must have been created on the device that is current at the call (LS_ERR_INVALID_ARG).
+ * All calls on one GPU share that GPU's array: calls that may overlap on the device (two
+ * streams, two stages) race and must be ordered by the caller.  Nothing in the array has to
+ * be zero at entry and its contents after the call are unspecified.
+ */
+#define LS_STATIC_SCRATCH_BYTES (16u << 20)
+ls_status ls_stage_decode_static(ls_stage* stage, const void* in, int batch, int max_ctx,
+                                 const ls_kv* kv, void* out, float* logits_out, void* hip_stream);
+
 /* ---- measurement ---------------------------------------------------------------------*/
 
 /* With profiling on, ls_stage_load_block brackets each copy and ls_stage_prefill brackets

@@ -28,6 +28,7 @@ if not os.path.exists(LIB_PATH):
 lib = C.CDLL(LIB_PATH)
 
 LS_ABI_VERSION = 1
+LS_STATIC_SCRATCH_BYTES = 16 << 20
 LS_DTYPE_F32, LS_DTYPE_BF16 = 0, 1
 LS_BLOCK_EMBED = -1
 LS_OP_NONE, LS_OP_NORM, LS_OP_GEMM_QKV = 0, 1, 2
@@ -78,6 +79,7 @@ _SIGS = {
     "ls_stage_reset_blocks": (C.c_int, [_P]),
     "ls_stage_prefill": (C.c_int, [_P, _P, _P, C.POINTER(C.c_int32), C.c_int, C.c_int, C.POINTER(ls_kv), _P, _P, _P]),
     "ls_stage_decode": (C.c_int, [_P, _P, C.c_int, C.c_int, C.POINTER(ls_kv), _P, _P, _P]),
+    "ls_stage_decode_static": (C.c_int, [_P, _P, C.c_int, C.c_int, C.POINTER(ls_kv), _P, _P, _P]),
     "ls_stage_check_prefill": (C.c_int, [_P, C.POINTER(C.c_int32), C.c_int, C.c_int]),
     "ls_stage_check_decode": (C.c_int, [_P, C.c_int, C.c_int]),
     "ls_stage_set_profiling": (C.c_int, [_P, C.c_int]),
@@ -259,9 +261,10 @@ class Stage:
         self._keep = (cu_dev, inp)
         return (out, logits) if want_logits else out
 
-    def decode(self, inp, batch: int, max_ctx: int, stream=None, want_logits=False, out=None):
+    def decode(self, inp, batch: int, max_ctx: int, stream=None, want_logits=False, out=None, static=False):
+        """static=True: ls_stage_decode_static (partial results in the library's static array)."""
         torch = self.torch
-        fn = lib.ls_stage_decode
+        fn = lib.ls_stage_decode_static if static else lib.ls_stage_decode
         if out is None:
             out = (torch.empty(batch, dtype=torch.int32, device=self.device) if self.last
                    else torch.empty(batch, self.shape.hidden, dtype=self.tdtype, device=self.device))

@@ -8,12 +8,42 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
+
+// Scratch of the entry point that allocates nothing (ls_stage_decode_static): the fp32
+// partial tiles of the decode GEMMs that split K across workgroups.  Every GPU the library
+// runs on holds its own copy of this array, at its own address, until the process ends.  In
+// host code the name is only a handle for hipGetSymbolAddress; kernels get the address that
+// call returned.
+static __device__ __align__(256) unsigned char scratch[LS_STATIC_SCRATCH_BYTES];
 
 namespace {
 
 thread_local char g_err[512] = "";
+
+// Address of `scratch` on each device, looked up once per device with that device current.
+constexpr int MAX_DEVICES = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[MAX_DEVICES] = {};
+
+hipError_t static_scratch_of_current_device(int* dev_out, void** ptr_out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= MAX_DEVICES) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    g_scratch_ptr[dev] = p;
+  }
+  *dev_out = dev;
+  *ptr_out = g_scratch_ptr[dev];
+  return hipSuccess;
+}
 
 ls_status fail(ls_status code, const char* fmt, ...) {
   va_list ap;
@@ -178,6 +208,8 @@ struct ls_stage {
   Carve w;
   std::vector<Block> blocks;  // [embed?] layers lo..hi-1 [head?]
   int layer0;                 // index in blocks of layer lo
+  int device;             // HIP device the stage was created on
+  void* static_scratch;   // this device's copy of the library's static scratch array
   bool profiling;
   bool compute_timed;
   int origin_block;  // first block copied with profiling on since the last reset, or -1
@@ -250,8 +282,16 @@ ls_status ls_stage_create(const ls_cfg* cfg, int lo, int hi, void* weight_slab, 
   Carve w = carve(cfg, lo, hi);
   if (ws_bytes < w.total) return fail(LS_ERR_OOM, "ls_stage_create: workspace too small");
 
+  int device = -1;
+  void* static_scratch = nullptr;
+  {
+    hipError_t e = static_scratch_of_current_device(&device, &static_scratch);
+    if (e != hipSuccess) return fail(LS_ERR_HIP, "ls_stage_create: address of the static scratch: %s", hipGetErrorString(e));
+  }
   ls_stage* s = new (std::nothrow) ls_stage();
   if (!s) return fail(LS_ERR_OOM, "ls_stage_create: host allocation failed");
+  s->device = device;
+  s->static_scratch = static_scratch;
   s->cfg = *cfg;
   s->lo = lo;
   s->hi = hi;
@@ -680,6 +720,26 @@ ls::GemmScratch workspace_scratch(const ls_stage* s) {
   return g;
 }
 
+// Largest split-K scratch any GEMM of one decode step over `rows` rows asks for.
+size_t decode_scratch_need(const ls_stage* s, int rows) {
+  const ls_cfg& c = s->cfg;
+  if (c.dtype != LS_DTYPE_BF16 || rows <= 16) return 0;
+  const int d = c.hidden, F = c.ffn, qd = c.n_q_heads * c.head_dim;
+  const int qkv_cols = (c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim;
+  size_t need = 0;
+  auto one = [&](int N, int K, bool glu) {
+    if (!ls::gemm_wide_supported(rows, N, K)) return;
+    const size_t b = ls::gemm_wide_workspace_bytes(rows, N, K, glu);
+    if (b > need) need = b;
+  };
+  one(qkv_cols, d, false);
+  one(d, qd, false);
+  one(F, d, true);
+  one(d, F, false);
+  if (s->last) one((int)c.vocab, d, false);
+  return need;
+}
+
 }  // namespace
 
 extern "C" {
@@ -712,6 +772,27 @@ ls_status ls_stage_decode(ls_stage* s, const void* in, int batch, int max_ctx, c
   if (rc != LS_OK) return rc;
   return forward(s, false, in, nullptr, batch, batch, 1, kv, out, logits_out, (hipStream_t)hip_stream,
                  workspace_scratch(s));
+}
+
+ls_status ls_stage_decode_static(ls_stage* s, const void* in, int batch, int max_ctx, const ls_kv* kv, void* out,
+                                 float* logits_out, void* hip_stream) {
+  ls_status rc = check_pointers("ls_stage_decode_static", s, in, kv, out, logits_out);
+  if (rc != LS_OK) return rc;
+  rc = check_decode("ls_stage_decode_static", s, batch, max_ctx);
+  if (rc != LS_OK) return rc;
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev != s->device)
+    return fail(LS_ERR_INVALID_ARG, "ls_stage_decode_static: the stage's device (%d) is not the current one", s->device);
+  const size_t need = decode_scratch_need(s, batch);
+  if (need > (size_t)LS_STATIC_SCRATCH_BYTES)
+    return fail(LS_ERR_OOM, "ls_stage_decode_static: this step needs %zu bytes of scratch, the static array holds %zu",
+                need, (size_t)LS_STATIC_SCRATCH_BYTES);
+  // the K-split partials of this step go to the device's static array: every workgroup writes
+  // its whole partial tile before the finishing kernel reads it, so nothing has to start at zero
+  ls::GemmScratch g;
+  g.splitk = (float*)s->static_scratch;
+  g.bytes = LS_STATIC_SCRATCH_BYTES;
+  return forward(s, false, in, nullptr, batch, batch, 1, kv, out, logits_out, (hipStream_t)hip_stream, g);
 }
 
 ls_status ls_stage_layer_times(ls_stage* s, float* copy_ms, float* compute_ms, float* copy_end_ms,
