@@ -35,12 +35,19 @@ namespace {
 #ifndef LS_GEMM_NS
 #define LS_GEMM_NS 2
 #endif
+#ifndef LS_GEMM_WAVES
+#define LS_GEMM_WAVES 8
+#endif
 constexpr int BM = 256, BN = 256, BK = LS_GEMM_BK;
+constexpr int NWAVE = LS_GEMM_WAVES;            // wavefronts per workgroup: 8 (2 x 4) or 4 (2 x 2)
+constexpr int WCOLS = NWAVE / 2;                // wavefronts side by side along N
+constexpr int TJ = BN / (WCOLS * 32);           // 32-column MFMA tiles per wavefront: 2 or 4
 constexpr int NS = LS_GEMM_NS;                  // ring of NS stages, NS-1 fills in flight
 constexpr int ROWB = BK * 2;                    // bytes per tile row
 constexpr int CH = ROWB / 16;                   // 16-byte chunks per row
 constexpr int RPI = 1024 / ROWB;                // rows per fill instruction
-constexpr int FI = 32 / RPI;                    // fill instructions per operand per wave
+constexpr int FROWS = BM / NWAVE;               // tile rows of each operand that one wavefront fills
+constexpr int FI = FROWS / RPI;                 // fill instructions per operand per wave
 constexpr int KK = BK / 16;                     // MFMA k-steps per stage
 constexpr int SH = (BK == 64) ? 1 : 2;          // swizzle: rows that share a bank group
 constexpr int TILE_BYTES = BM * ROWB;           // per operand tile
@@ -56,24 +63,51 @@ __device__ __forceinline__ int swz(int row, int chunk) {
 }
 
 template <int EPI>
-__global__ void __launch_bounds__(512, 1)
+__global__ void __launch_bounds__(NWAVE * 64, 1)
 k_gemm_mfma(const bf16* __restrict__ A, const bf16* __restrict__ W, int M, int N, int K,
             void* __restrict__ outv, float* __restrict__ resid, int tiles_m, int tiles_n) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   constexpr bool GLU = (EPI == EPI_SWIGLU);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave >> 2, wn = wave & 3;
+  const int wm = wave / WCOLS, wn = wave % WCOLS;
 
-  // ---- workgroup id -> tile, XCD-aware and grouped along M
+  // ---- workgroup id -> tile
   const int nt = tiles_m * tiles_n;
+#ifndef LS_GEMM_MAP
+#define LS_GEMM_MAP 0
+#endif
+#if LS_GEMM_MAP == 0
   const int per_xcd = (nt + 7) >> 3;
   const int l = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+#else
+  // chunks of 32 consecutive tiles go round-robin over the 8 XCDs
+  const int slot = blockIdx.x >> 3;
+  const int l = ((slot >> 5) << 8) + ((blockIdx.x & 7) << 5) + (slot & 31);
+#endif
   if (l >= nt) return;
+#if LS_GEMM_MAP < 2
   const int in_group = GROUP_M * tiles_n;
   const int first_m = (l / in_group) * GROUP_M;
   const int gsz = min(tiles_m - first_m, GROUP_M);
   const int tm = first_m + (l % in_group) % gsz;
   const int tn = (l % in_group) / gsz;
+#else
+  // two-level order: groups of 16 tile rows; inside a group, columns of 8 tiles; inside a
+  // column, patches of 4 rows, row index fastest.  32 consecutive tiles are a 4 x 8 patch, 256
+  // consecutive tiles a 16 x 16 block of the output (ragged edges shrink the pieces).
+  const int sg_tiles = 16 * tiles_n;
+  const int g = min(l / sg_tiles, (tiles_m - 1) >> 4);
+  const int R = min(16, tiles_m - 16 * g);
+  const int li = l - g * sg_tiles;
+  const int c = min(li / (R * 8), (tiles_n - 1) >> 3);
+  const int w = min(8, tiles_n - 8 * c);
+  const int lj = li - c * R * 8;
+  const int pm = min(lj / (4 * w), (R - 1) >> 2);
+  const int rr = min(4, R - 4 * pm);
+  const int lk = lj - pm * 4 * w;
+  const int tm = 16 * g + 4 * pm + lk % rr;
+  const int tn = 8 * c + lk / rr;
+#endif
   const int m0 = tm * BM;
   const int n0 = GLU ? tn * (BN / 2) : tn * BN;  // GLU: 128 output columns per tile
 
@@ -83,7 +117,7 @@ k_gemm_mfma(const bf16* __restrict__ A, const bf16* __restrict__ W, int M, int N
   const bf16* wp[FI];
 #pragma unroll
   for (int i = 0; i < FI; ++i) {
-    const int row = wave * 32 + i * RPI + lane / CH;
+    const int row = wave * FROWS + i * RPI + lane / CH;
     const int c = (lane % CH) ^ ((row >> SH) & (CH - 1));
     const int am = min(m0 + row, M - 1);
     ap[i] = A + (size_t)am * K + c * 8;
@@ -99,27 +133,27 @@ k_gemm_mfma(const bf16* __restrict__ A, const bf16* __restrict__ W, int M, int N
     }
     wp[i] = W + (size_t)wrow * K + c * 8;
   }
-  f32x16 acc[4][2];
+  f32x16 acc[4][TJ];
 #pragma unroll
   for (int i = 0; i < 4; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < TJ; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
   const int lr = lane & 31, lh = lane >> 5;
   const int KT = K / BK;
   // LDS byte offsets of this lane's operand reads
-  int a_off[KK][4], b_off[KK][2];
+  int a_off[KK][4], b_off[KK][TJ];
 #pragma unroll
   for (int kk = 0; kk < KK; ++kk) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) a_off[kk][i] = swz(wm * 128 + i * 32 + lr, kk * 2 + lh);
 #pragma unroll
-    for (int j = 0; j < 2; ++j) b_off[kk][j] = TILE_BYTES + swz(wn * 64 + j * 32 + lr, kk * 2 + lh);
+    for (int j = 0; j < TJ; ++j) b_off[kk][j] = TILE_BYTES + swz(wn * (TJ * 32) + j * 32 + lr, kk * 2 + lh);
   }
   typedef __attribute__((address_space(3))) void lds_void;
-  const int fill_off = (wave * 32) * ROWB;  // this wave's first row inside an operand tile
+  const int fill_off = (wave * FROWS) * ROWB;  // this wave's first row inside an operand tile
 
 #define LS_FILL_TILE(buf, k0)                                                                          \
   _Pragma("unroll") for (int i = 0; i < FI; ++i) {                                                     \
@@ -134,24 +168,24 @@ k_gemm_mfma(const bf16* __restrict__ A, const bf16* __restrict__ W, int M, int N
   {                                                                                                \
     _Pragma("unroll") for (int i = 0; i < 4; ++i)                                                  \
       af[set][i] = *reinterpret_cast<const bf16x8*>(smem + (buf) * STAGE_BYTES + a_off[kk][i]); \
-    _Pragma("unroll") for (int j = 0; j < 2; ++j)                                                  \
+    _Pragma("unroll") for (int j = 0; j < TJ; ++j)                                                 \
       bfr[set][j] = *reinterpret_cast<const bf16x8*>(smem + (buf) * STAGE_BYTES + b_off[kk][j]); \
   }
 #define LS_MFMA_STEP(set)                                                                          \
   _Pragma("unroll") for (int i = 0; i < 4; ++i)                                                    \
-    _Pragma("unroll") for (int j = 0; j < 2; ++j)                                                  \
+    _Pragma("unroll") for (int j = 0; j < TJ; ++j)                                                 \
       acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[set][i], bfr[set][j], acc[i][j], 0, 0, 0);
   // within a k-step the six fragment reads of the next k-step are spread between the eight
   // MFMAs (one read after each of the first six) instead of being issued as one burst
 #define LS_INTERLEAVE()                                                         \
-  _Pragma("unroll") for (int g_ = 0; g_ < 6; ++g_) {                            \
+  _Pragma("unroll") for (int g_ = 0; g_ < 4 + TJ; ++g_) {                       \
     __builtin_amdgcn_sched_group_barrier(0x008, 1, 0); /* one MFMA */           \
     __builtin_amdgcn_sched_group_barrier(0x100, 1, 0); /* one LDS read */       \
   }                                                                             \
-  __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+  __builtin_amdgcn_sched_group_barrier(0x008, 4 * TJ - (4 + TJ), 0);
 #define LS_COMPUTE_TILE(buf)                                    \
   {                                                             \
-    bf16x8 af[2][4], bfr[2][2];                                 \
+    bf16x8 af[2][4], bfr[2][TJ];                                \
     LS_READ_FRAGS(buf, 0, 0)                                    \
     __builtin_amdgcn_sched_barrier(0);                          \
     _Pragma("unroll") for (int kk = 0; kk < KK; ++kk) {         \
@@ -194,6 +228,34 @@ k_gemm_mfma(const bf16* __restrict__ A, const bf16* __restrict__ W, int M, int N
 #undef LS_STEP_BARRIER
 
   // ---- epilogue
+  if constexpr (EPI == EPI_RESID) {
+    // fp32 read-modify-write of the residual rows.  A store to `resid` may alias a later load
+    // as far as the compiler can tell, so "resid[o] += acc" element by element would wait one
+    // memory round trip per element; here the 16 old values of the NEXT 32 x 32 tile are
+    // requested before the current tile's sums are stored, so every lane always has 16 loads in
+    // flight behind its stores.
+    float old[2][16];
+    const int ncol = n0 + wn * (TJ * 32) + lr;
+#define LS_RESID_LOAD(t, set)                                                                       \
+  _Pragma("unroll") for (int r = 0; r < 16; ++r) {                                                  \
+    const int m_ = m0 + wm * 128 + ((t) / TJ) * 32 + 8 * (r >> 2) + 4 * lh + (r & 3);               \
+    const int n_ = ncol + ((t) % TJ) * 32;                                                          \
+    old[set][r] = (m_ < M && n_ < N) ? resid[(size_t)m_ * N + n_] : 0.f;                            \
+  }
+    LS_RESID_LOAD(0, 0)
+#pragma unroll
+    for (int t = 0; t < 4 * TJ; ++t) {
+      if (t + 1 < 4 * TJ) LS_RESID_LOAD(t + 1, (t + 1) & 1)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int m = m0 + wm * 128 + (t / TJ) * 32 + 8 * (r >> 2) + 4 * lh + (r & 3);
+        const int n = ncol + (t % TJ) * 32;
+        if (m < M && n < N) resid[(size_t)m * N + n] = old[t & 1][r] + acc[t / TJ][t % TJ][r];
+      }
+    }
+#undef LS_RESID_LOAD
+    return;
+  }
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
 #pragma unroll
@@ -201,16 +263,18 @@ k_gemm_mfma(const bf16* __restrict__ A, const bf16* __restrict__ W, int M, int N
       const int m = m0 + wm * 128 + i * 32 + 8 * (r >> 2) + 4 * lh + (r & 3);
       if (m >= M) continue;
       if constexpr (GLU) {
-        const int n = n0 + wn * 32 + lr;
-        if (n < N) ((bf16*)outv)[(size_t)m * N + n] = (bf16)(silu_f(acc[i][0][r]) * acc[i][1][r]);
+#pragma unroll
+        for (int jj = 0; jj < TJ / 2; ++jj) {
+          const int n = n0 + wn * (TJ * 16) + jj * 32 + lr;
+          if (n < N) ((bf16*)outv)[(size_t)m * N + n] = (bf16)(silu_f(acc[i][2 * jj][r]) * acc[i][2 * jj + 1][r]);
+        }
       } else {
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-          const int n = n0 + wn * 64 + j * 32 + lr;
+        for (int j = 0; j < TJ; ++j) {
+          const int n = n0 + wn * (TJ * 32) + j * 32 + lr;
           if (n >= N) continue;
           const size_t o = (size_t)m * N + n;
           if constexpr (EPI == EPI_STORE) ((bf16*)outv)[o] = (bf16)acc[i][j][r];
-          else if constexpr (EPI == EPI_RESID) resid[o] += acc[i][j][r];
           else ((float*)outv)[o] = acc[i][j][r];
         }
       }
@@ -226,8 +290,12 @@ void launch_t(const void* A, const void* W, int M, int N, int K, void* out, floa
   const int ncols = (EPI == EPI_SWIGLU) ? BN / 2 : BN;
   const int tiles_n = (N + ncols - 1) / ncols;
   const int nt = tiles_m * tiles_n;
+#if LS_GEMM_MAP == 0
   const int grid = ((nt + 7) / 8) * 8;
-  launch_kernel(k_gemm_mfma<EPI>, dim3(grid), dim3(512), SMEM_BYTES, st, (const bf16*)A, (const bf16*)W, M, N, K, out,
+#else
+  const int grid = ((nt + 255) / 256) * 256;
+#endif
+  launch_kernel(k_gemm_mfma<EPI>, dim3(grid), dim3(NWAVE * 64), SMEM_BYTES, st, (const bf16*)A, (const bf16*)W, M, N, K, out,
                 resid, tiles_m, tiles_n);
 }
 
