@@ -6,15 +6,27 @@
 // tiles of 64, double-buffered in LDS.  Both products are computed transposed so that all
 // per-row softmax state is per-lane:
 //   S^T[key][q] = K[key][:] . Q[q][:]      MFMA A = K tile rows,  B = Q rows (registers)
-//   O^T[d][q]  += V^T[d][key] . P^T[key][q] MFMA A = V^T tile rows, B = P^T
+//   O^T[d][q]  += V^T[d][key] . P^T[key][q] MFMA A = V^T,          B = P^T
 // In a v_mfma_f32_32x32x16_bf16 result a lane holds column q = lane%32 and 16 rows
 // 8*(i/4) + 4*(lane/32) + i%4: one query row per lane, so the row maximum / sum are
 // in-lane reductions plus one exchange with lane^32, and the eight P values a lane holds
 // for a 16-key step are exactly a B operand whose k index runs over keys
-// {4h..4h+3, 8+4h..8+4h+3} (h = lane/32); the V^T operand is read with the same key order.
-// V is transposed on its way into LDS ([d][key], 8-byte granules XOR-swizzled by d/2).
-// Keys beyond a row's position get a score of -inf before the exponential; cache rows at or
-// beyond the sequence length are never read (indices are clamped to the last valid row).
+// {4h..4h+3, 8+4h..8+4h+3} (h = lane/32).
+//
+// K and V tiles lie in LDS as they lie in the cache, row-major [key][head_dim], and arrive
+// there straight from global memory (global_load_lds_dwordx4: no staging registers, no LDS
+// store instructions).  The V^T operand is produced by the LDS read itself: with
+// ds_read_b64_tr_b16 the 16 lanes of a group hand in the addresses of a 4-key x 16-dim block
+// (lane j: key j/4, dims 4(j%4)..4(j%4)+3) and lane j receives that block's column j, i.e.
+// the four keys' values at ONE dim -- half an A operand of V^T in the key order above; two such
+// reads make one operand.  16-byte chunks of a row are XOR-swizzled by a permutation of the
+// key's low bits chosen so that both access patterns spread over all banks: the 32 rows of a
+// K operand read (one 16-byte chunk per row) and the 4 rows x 32 bytes of a transposing read.
+//
+// A wavefront whose 32 rows all lie above a key tile skips that tile's arithmetic (it still
+// takes part in the fills and barriers); the output rescale is skipped when no row's running
+// maximum moved.  Keys beyond a row's position get a score of -inf before the exponential;
+// cache rows at or beyond the sequence length are never read (indices are clamped).
 #include "kernels.hpp"
 #include "device_util.hpp"
 
@@ -29,13 +41,17 @@ __global__ void __launch_bounds__(256, 2)
 k_attn_prefill(const bf16* __restrict__ qkv, int qkv_stride, const bf16* __restrict__ kc,
                const bf16* __restrict__ vc, const int32_t* __restrict__ cu, int hq, int hkv, int max_seq,
                bf16* __restrict__ out) {
-  constexpr int CPR = HD / 8;            // 16-byte chunks per K row
-  constexpr int KT_BYTES = BKV * HD * 2;  // K tile; the V^T tile has the same size
-  constexpr int KLD = (BKV * CPR) / 256;  // K chunks per thread per tile
-  constexpr int VLD = (32 * CPR) / 256;   // V work items (key pair x 8 dims) per thread per tile
-  constexpr int DT = HD / 32;            // 32-row tiles of O^T
-  constexpr int KS = HD / 16;            // k-steps of the score product
-  __shared__ __attribute__((aligned(16))) unsigned char smem[2][2 * KT_BYTES];
+  constexpr int ROWB = HD * 2;            // bytes per K / V row
+  constexpr int CPR = HD / 8;             // 16-byte chunks per row: 16 or 8
+  constexpr int TILE = BKV * ROWB;        // one K or V tile
+  constexpr int RPI = 1024 / ROWB;        // rows one fill instruction covers: 4 or 8
+  constexpr int FI = BKV / (4 * RPI);     // fill instructions per wavefront, tile and operand
+  constexpr int DT = HD / 32;             // 32-row tiles of O^T
+  constexpr int KS = HD / 16;             // k-steps of the score product
+  __shared__ __attribute__((aligned(1024))) unsigned char smem[2][2 * TILE];
+  typedef __attribute__((address_space(3))) void lds_void;
+  typedef short s16x4 __attribute__((ext_vector_type(4)));
+  typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 
   const int b = blockIdx.z, h = blockIdx.y;
   const int row0 = cu[b], len = cu[b + 1] - row0;
@@ -44,10 +60,14 @@ k_attn_prefill(const bf16* __restrict__ qkv, int qkv_stride, const bf16* __restr
   if (qt < 0) return;
   const int q0 = qt * BQ;
   const int kh = h / (hq / hkv);
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // in a scalar register: what depends on it is wave-uniform
   const int lr = lane & 31, lh = lane >> 5;
   const bf16* kb = kc + ((size_t)b * hkv + kh) * max_seq * HD;
   const bf16* vb = vc + ((size_t)b * hkv + kh) * max_seq * HD;
+
+  // chunk swizzle of row `key`: a permutation of the key's low bits (see the file header)
+  auto swz = [](int key) { return HD == 128 ? (((key & 3) << 2) | ((key >> 2) & 3)) : (((key & 3) << 1) | ((key >> 2) & 1)); };
 
   // this lane's query row as B operands (one 8-wide k slice per k-step)
   const int qpos = q0 + wave * 32 + lr;            // position of this lane's query row
@@ -67,132 +87,131 @@ k_attn_prefill(const bf16* __restrict__ qkv, int qkv_stride, const bf16* __restr
 
   const int kv_end = min(q0 + BQ, len);          // keys this tile can see
   const int ntk = (kv_end + BKV - 1) / BKV;
+  const int wave_last = q0 + wave * 32 + 31;     // last position any row of this wavefront has
 
-  // staging registers for the next K / V tile
-  u32x4 kreg[KLD], vreg[VLD][2];
-#define LS_LOAD_KV(t0)                                                                    \
-  {                                                                                       \
-    _Pragma("unroll") for (int i_ = 0; i_ < KLD; ++i_) {                                  \
-      const int w_ = tid + 256 * i_;                                                      \
-      const int key_ = min((t0) + w_ / CPR, len - 1);                                     \
-      kreg[i_] = *reinterpret_cast<const u32x4*>(kb + (size_t)key_ * HD + (w_ % CPR) * 8); \
-    }                                                                                     \
-    _Pragma("unroll") for (int i_ = 0; i_ < VLD; ++i_) {                                  \
-      const int w_ = tid + 256 * i_;                                                      \
-      const int k0_ = (t0) + 2 * (w_ / CPR);                                              \
-      vreg[i_][0] = *reinterpret_cast<const u32x4*>(vb + (size_t)min(k0_, len - 1) * HD + (w_ % CPR) * 8);     \
-      vreg[i_][1] = *reinterpret_cast<const u32x4*>(vb + (size_t)min(k0_ + 1, len - 1) * HD + (w_ % CPR) * 8); \
-    }                                                                                     \
+  // ---- fills: wavefront w brings rows (w*FI + i)*RPI .. +RPI-1 of both tiles; the lane that
+  // fills physical chunk p of row r fetches logical chunk p ^ swz(r)
+  const int frow = lane / CPR, fchunk = lane % CPR;
+#define LS_FILL(buf, t0)                                                                          \
+  _Pragma("unroll") for (int i_ = 0; i_ < FI; ++i_) {                                             \
+    const int r_ = (wave * FI + i_) * RPI + frow;                                                 \
+    const size_t g_ = (size_t)min((t0) + r_, len - 1) * HD + ((fchunk ^ swz(r_)) << 3);            \
+    __builtin_amdgcn_global_load_lds((const void*)(kb + g_),                                      \
+        (lds_void*)(smem[buf] + (wave * FI + i_) * 1024), 16, 0, 0);                              \
+    __builtin_amdgcn_global_load_lds((const void*)(vb + g_),                                      \
+        (lds_void*)(smem[buf] + TILE + (wave * FI + i_) * 1024), 16, 0, 0);                       \
   }
-#define LS_STORE_KV(buf)                                                                  \
-  {                                                                                       \
-    unsigned char* ks_ = smem[buf];                                                       \
-    unsigned char* vs_ = smem[buf] + KT_BYTES;                                            \
-    _Pragma("unroll") for (int i_ = 0; i_ < KLD; ++i_) {                                  \
-      const int w_ = tid + 256 * i_;                                                      \
-      const int r_ = w_ / CPR, c_ = w_ % CPR;                                             \
-      const int sw_ = (HD == 128) ? (r_ & 15) : ((r_ >> 1) & 7);                          \
-      *reinterpret_cast<u32x4*>(ks_ + r_ * (HD * 2) + ((c_ ^ sw_) << 4)) = kreg[i_];      \
-    }                                                                                     \
-    _Pragma("unroll") for (int i_ = 0; i_ < VLD; ++i_) {                                  \
-      const int w_ = tid + 256 * i_;                                                      \
-      const int kp_ = w_ / CPR, dc_ = w_ % CPR;                                           \
-      _Pragma("unroll") for (int e_ = 0; e_ < 8; ++e_) {                                  \
-        const int d_ = dc_ * 8 + e_;                                                      \
-        const unsigned lo_ = (vreg[i_][0][e_ >> 1] >> ((e_ & 1) * 16)) & 0xffffu;         \
-        const unsigned hi_ = (vreg[i_][1][e_ >> 1] >> ((e_ & 1) * 16)) & 0xffffu;         \
-        const int g_ = (kp_ >> 1) ^ ((d_ >> 1) & 15);                                     \
-        *reinterpret_cast<unsigned*>(vs_ + d_ * 128 + g_ * 8 + (kp_ & 1) * 4) = lo_ | (hi_ << 16); \
-      }                                                                                   \
-    }                                                                                     \
-  }
+  // all fills this wavefront issued have landed, then the workgroup meets
+#define LS_TILE_BARRIER()                    \
+  asm volatile("" ::: "memory");             \
+  __builtin_amdgcn_s_waitcnt(0x0F70);        \
+  __builtin_amdgcn_s_waitcnt(0xC07F);        \
+  __builtin_amdgcn_sched_barrier(0);         \
+  __builtin_amdgcn_s_barrier();              \
+  __builtin_amdgcn_sched_barrier(0);         \
+  asm volatile("" ::: "memory");
 
-  LS_LOAD_KV(0)
-  LS_STORE_KV(0)
-  __syncthreads();
+  // LDS byte offsets of this lane's operand reads inside a tile
+  const int ksw = swz(lr);                        // rows lr and 32 + lr share their low bits
+  const int k_row = lr * ROWB;
+  // transposing read: group g = lane/16 covers dims 16*(g&1).., keys 4*(g>>1) + j/4; lane j of
+  // the group addresses dims 4*(j%4)..+3 of its key
+  const int tj = lane & 15, tg = lane >> 4;
+  const int v_key = 4 * (tg >> 1) + (tj >> 2);    // + 16 kp (+ 8 for the second half)
+  const int v_col = 16 * (tg & 1) + 4 * (tj & 3);  // + 32 dt: first dim this lane addresses
+  const int v_sub = (v_col & 7) * 2;              // byte offset inside its 16-byte chunk
+
+  LS_FILL(0, 0)
+  LS_TILE_BARRIER()
   for (int t = 0; t < ntk; ++t) {
     const int buf = t & 1;
     const int t0 = t * BKV;
-    if (t + 1 < ntk) LS_LOAD_KV(t0 + BKV)
+    // buffer buf^1 was last read in iteration t-1, which every wavefront has left
+    if (t + 1 < ntk) LS_FILL(buf ^ 1, t0 + BKV)
     const unsigned char* ks_ = smem[buf];
-    const unsigned char* vs_ = smem[buf] + KT_BYTES;
+    const unsigned char* vs_ = smem[buf] + TILE;
 
-    // ---- S^T = K Q^T for the 64 keys of the tile (two 32-key row tiles)
-    f32x16 s[2];
+    if (t0 <= wave_last) {  // wave-uniform: some row of this wavefront sees some key of the tile
+      // ---- S^T = K Q^T for the 64 keys of the tile (two 32-key row tiles)
+      f32x16 s[2];
 #pragma unroll
-    for (int kt = 0; kt < 2; ++kt) {
+      for (int kt = 0; kt < 2; ++kt) {
 #pragma unroll
-      for (int i = 0; i < 16; ++i) s[kt][i] = 0.f;
-      const int r = kt * 32 + lr;
-      const int sw = (HD == 128) ? (r & 15) : ((r >> 1) & 7);
+        for (int i = 0; i < 16; ++i) s[kt][i] = 0.f;
 #pragma unroll
-      for (int ksn = 0; ksn < KS; ++ksn) {
-        const bf16x8 kf = *reinterpret_cast<const bf16x8*>(ks_ + r * (HD * 2) + (((ksn * 2 + lh) ^ sw) << 4));
-        s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ksn], s[kt], 0, 0, 0);
+        for (int ksn = 0; ksn < KS; ++ksn) {
+          const bf16x8 kf = *reinterpret_cast<const bf16x8*>(ks_ + kt * 32 * ROWB + k_row + (((ksn * 2 + lh) ^ ksw) << 4));
+          s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ksn], s[kt], 0, 0, 0);
+        }
       }
-    }
-    // ---- causal mask, online softmax (all for this lane's query row).  Scores stay unscaled:
-    // the running maximum is kept in score units and the scale (with the change to base 2)
-    // is folded into the exponential's argument, p = 2^(c s - c m).
-    // `diag` is the same for the whole wavefront: tiles left of the diagonal skip the mask.
-    const bool diag = __builtin_amdgcn_readfirstlane((int)((t0 + BKV - 1) > (q0 + wave * 32))) != 0;
-    float mx = -INFINITY;
-    if (diag) {
+      // ---- causal mask, online softmax (all for this lane's query row).  Scores stay unscaled:
+      // the running maximum is kept in score units and the scale (with the change to base 2)
+      // is folded into the exponential's argument, p = 2^(c s - c m).
+      // `diag` is the same for the whole wavefront: tiles left of the diagonal skip the mask.
+      const bool diag = (t0 + BKV - 1) > (q0 + wave * 32);
+      float mx = -INFINITY;
+      if (diag) {
+#pragma unroll
+        for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) {
+            const int key = t0 + kt * 32 + 8 * (i >> 2) + 4 * lh + (i & 3);
+            const float v = key > qpos ? -INFINITY : s[kt][i];
+            s[kt][i] = v;
+            mx = fmaxf(mx, v);
+          }
+      } else {
+#pragma unroll
+        for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[kt][i]);
+      }
+      mx = fmaxf(mx, __shfl_xor(mx, 32));
+      const float m_new = fmaxf(m_run, mx);  // finite from the first tile on: key 0 is visible
+      const float mc = m_new * c;
+      float psum = 0.f;
+      bf16x8 pf[4];
 #pragma unroll
       for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
-          const int key = t0 + kt * 32 + 8 * (i >> 2) + 4 * lh + (i & 3);
-          const float v = key > qpos ? -INFINITY : s[kt][i];
-          s[kt][i] = v;
-          mx = fmaxf(mx, v);
+          const float p = __builtin_amdgcn_exp2f(fmaf(s[kt][i], c, -mc));
+          psum += p;
+          pf[kt * 2 + (i >> 3)][i & 7] = (bf16)p;
         }
-    } else {
+      // the running maximum moved for some row of the wavefront: rescale sums and outputs
+      if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0) {
+        const float corr = __builtin_amdgcn_exp2f((m_run - m_new) * c);
+        l_run *= corr;
 #pragma unroll
-      for (int kt = 0; kt < 2; ++kt)
+        for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[kt][i]);
-    }
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
-    const float m_new = fmaxf(m_run, mx);  // finite from the first tile on: key 0 is visible
-    const float corr = __builtin_amdgcn_exp2f((m_run - m_new) * c);
-    const float mc = m_new * c;
-    float psum = 0.f;
-    bf16x8 pf[4];
-#pragma unroll
-    for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const float p = __builtin_amdgcn_exp2f(fmaf(s[kt][i], c, -mc));
-        psum += p;
-        pf[kt * 2 + (i >> 3)][i & 7] = (bf16)p;
+          for (int i = 0; i < 16; ++i) o[dt][i] *= corr;
+        m_run = m_new;
       }
-    l_run = l_run * corr + psum;
-    m_run = m_new;
-#pragma unroll
-    for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) o[dt][i] *= corr;
-    // ---- O^T += V^T P^T
-#pragma unroll
-    for (int dt = 0; dt < DT; ++dt) {
-      const int d = dt * 32 + lr;
-      const int sw = (d >> 1) & 15;
+      l_run += psum;
+      // ---- O^T += V^T P^T; the V^T operand comes out of two transposing reads
 #pragma unroll
       for (int kp = 0; kp < 4; ++kp) {  // 16-key steps
-        bf16x4 lo = *reinterpret_cast<const bf16x4*>(vs_ + d * 128 + (((kp * 4 + lh) ^ sw) << 3));
-        bf16x4 hi = *reinterpret_cast<const bf16x4*>(vs_ + d * 128 + (((kp * 4 + 2 + lh) ^ sw) << 3));
-        bf16x8 vf;
+        const int key0 = 16 * kp + v_key, key1 = key0 + 8;
+        const int sw0 = swz(key0), sw1 = swz(key1);
 #pragma unroll
-        for (int e = 0; e < 4; ++e) { vf[e] = lo[e]; vf[4 + e] = hi[e]; }
-        o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[kp], o[dt], 0, 0, 0);
+        for (int dt = 0; dt < DT; ++dt) {
+          const int ch = (32 * dt + v_col) >> 3;  // logical 16-byte chunk of the addressed dims
+          const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+              (lds_s16x4*)(vs_ + key0 * ROWB + ((ch ^ sw0) << 4) + v_sub));
+          const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+              (lds_s16x4*)(vs_ + key1 * ROWB + ((ch ^ sw1) << 4) + v_sub));
+          typedef short s16x8 __attribute__((ext_vector_type(8)));
+          const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+          o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both), pf[kp], o[dt], 0, 0, 0);
+        }
       }
     }
-    if (t + 1 < ntk) LS_STORE_KV(buf ^ 1)
-    __syncthreads();
+    LS_TILE_BARRIER()
   }
-#undef LS_LOAD_KV
-#undef LS_STORE_KV
+#undef LS_FILL
+#undef LS_TILE_BARRIER
 
   // ---- normalise and store this lane's query row
   const float l_tot = l_run + __shfl_xor(l_run, 32);
