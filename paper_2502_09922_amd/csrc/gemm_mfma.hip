@@ -208,6 +208,53 @@ k_gemm_mfma(const bf16* __restrict__ A, const bf16* __restrict__ W, int M, int N
   __builtin_amdgcn_sched_barrier(0);         \
   asm volatile("" ::: "memory");
 
+#ifndef LS_GEMM_ROT
+#define LS_GEMM_ROT 1
+#endif
+#if LS_GEMM_ROT
+  // The loop is rotated by one MFMA group: the barrier that hands over the next stage sits
+  // BEFORE the last group of a k-step, so that group's MFMAs run while the first operand
+  // fragments of the next stage are on their way from LDS, and neither wavefront of a SIMD
+  // starts a k-step by waiting for LDS.  Right after the barrier the stage just read out is
+  // refilled, which leaves its fills a whole k-step to land, as before.
+  static_assert(NS == 2 && KK % 2 == 0, "the rotated loop alternates two stages and two fragment sets");
+  {
+    bf16x8 af[2][4], bfr[2][TJ];
+    LS_FILL_TILE(0, 0)
+    LS_STEP_BARRIER(0x0F70)
+    if (KT > 1) LS_FILL_TILE(1, BK)
+    LS_READ_FRAGS(0, 0, 0)
+    __builtin_amdgcn_sched_barrier(0);
+    for (int kt = 0; kt + 1 < KT; ++kt) {
+      const int buf = kt & 1;
+#pragma unroll
+      for (int kk = 0; kk + 1 < KK; ++kk) {
+        LS_READ_FRAGS(buf, kk + 1, (kk + 1) & 1)
+        LS_MFMA_STEP(kk & 1)
+        LS_INTERLEAVE()
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      // stage kt+1 has landed for every wavefront, and every wavefront has read all of stage kt
+      LS_STEP_BARRIER(0x0F70)
+      if (kt + 2 < KT) LS_FILL_TILE(buf, (kt + 2) * BK)
+      LS_READ_FRAGS(buf ^ 1, 0, 0)
+      LS_MFMA_STEP(1)
+      LS_INTERLEAVE()
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    {  // the last k-step has nothing to hand over
+      const int buf = (KT - 1) & 1;
+#pragma unroll
+      for (int kk = 0; kk + 1 < KK; ++kk) {
+        LS_READ_FRAGS(buf, kk + 1, (kk + 1) & 1)
+        LS_MFMA_STEP(kk & 1)
+        LS_INTERLEAVE()
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      LS_MFMA_STEP(1)
+    }
+  }
+#else
 #pragma unroll
   for (int s = 0; s < NS - 1; ++s)
     if (s < KT) LS_FILL_TILE(s, s * BK)
@@ -220,6 +267,7 @@ k_gemm_mfma(const bf16* __restrict__ A, const bf16* __restrict__ W, int M, int N
     LS_COMPUTE_TILE(buf)
     if (more) { LS_STEP_BARRIER(WAIT_KEEP) } else { LS_STEP_BARRIER(0x0F70) }
   }
+#endif
 #undef LS_FILL_TILE
 #undef LS_COMPUTE_TILE
 #undef LS_INTERLEAVE
