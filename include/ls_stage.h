@@ -234,8 +234,9 @@ ls_status ls_stage_check_decode(const ls_stage* stage, int batch, int max_ctx);
  * fp32 partial tiles: in a static device array of LS_STATIC_SCRATCH_BYTES inside the library
  * (one copy per GPU, held until the process ends) instead of the caller's workspace.  The
  * call allocates and frees nothing.  A step whose largest GEMM needs more than the array
- * holds (rows x columns x K-splits x 4 bytes; 16 MiB covers 64 rows of the 7B-, 13B- and
- * 70B-shaped layers and a 32000-entry head) is LS_ERR_OOM and enqueues nothing; the stage
+ * holds (rows x columns x K-splits across workgroups x 4 bytes; 16 MiB covers 64 rows of the
+ * 13B- and 70B-shaped layers, 32 rows of the 7B-shaped ones and a 32000-entry head, which
+ * needs none) is LS_ERR_OOM and enqueues nothing; the stage
  * must have been created on the device that is current at the call (LS_ERR_INVALID_ARG).
  * All calls on one GPU share that GPU's array: calls that may overlap on the device (two
  * streams, two stages) race and must be ordered by the caller.  Nothing in the array has to

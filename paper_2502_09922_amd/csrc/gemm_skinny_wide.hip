@@ -20,14 +20,78 @@
 
 namespace ls {
 
+int gemm_wide_splits(int N, int K);
+
 namespace {
 
 constexpr int WAVES = 4;
 
-template <int MT, bool GLU>
+// Epilogue of one wavefront's accumulators when no other workgroup shares its K range: the same
+// arithmetic as k_wide_finish, applied in registers.  A lane holds row m = lr + 16 t and the
+// four columns n .. n+3; `inv` is the folded RMSNorm's 1/rms of row m (1 without a folded norm).
+template <int EPI, int MT, int NW>
+__device__ __forceinline__ void wide_epilogue(const f32x4 (&acc)[NW][MT], const float (&inv)[MT], int M, int N, int n,
+                                              int lr, int lg, void* __restrict__ outv, float* __restrict__ resid,
+                                              const SkinnyFusion& fu) {
+#pragma unroll
+  for (int t = 0; t < MT; ++t) {
+    const int m = lr + 16 * t;
+    const bool live = m < M;
+    const size_t o = (size_t)(live ? m : 0) * N + n;
+    const f32x4 v = acc[0][t] * inv[t];
+    if constexpr (EPI == EPI_STORE) {
+      bf16x4 y;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) y[e] = (bf16)v[e];
+      if (live) *reinterpret_cast<bf16x4*>((bf16*)outv + o) = y;
+    } else if constexpr (EPI == EPI_RESID) {
+      f32x4 xn = {0.f, 0.f, 0.f, 0.f};
+      if (live) {
+        xn = *reinterpret_cast<const f32x4*>(resid + o) + v;
+        *reinterpret_cast<f32x4*>(resid + o) = xn;
+      }
+      if (fu.xb_out) {
+        f32x4 gain = {1.f, 1.f, 1.f, 1.f};
+        if (fu.gamma_out) {
+          const bf16x4 g = *reinterpret_cast<const bf16x4*>(fu.gamma_out + n);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) gain[e] = (float)g[e];
+        }
+        bf16x4 y;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) y[e] = (bf16)(xn[e] * gain[e]);
+        if (live) *reinterpret_cast<bf16x4*>(fu.xb_out + o) = y;
+        // sum of squares of the wavefront's 16-column tile: four columns in order in the lane,
+        // then the four lane groups by a fixed exchange
+        float ss = ((xn[0] * xn[0] + xn[1] * xn[1]) + xn[2] * xn[2]) + xn[3] * xn[3];
+        ss += __shfl_xor(ss, 16);
+        ss += __shfl_xor(ss, 32);
+        if (live && lg == 0) fu.ss_out[(size_t)m * (N >> 4) + (n >> 4)] = ss;
+      }
+    } else if constexpr (EPI == EPI_SWIGLU) {
+      const f32x4 u = acc[NW - 1][t] * inv[t];
+      bf16x4 y;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) y[e] = (bf16)(silu_f(v[e]) * u[e]);
+      if (live) *reinterpret_cast<bf16x4*>((bf16*)outv + o) = y;
+    } else {
+      if (live) *reinterpret_cast<f32x4*>((float*)outv + o) = v;
+    }
+  }
+}
+
+// With gridDim.y == 1 the workgroup owns its columns' whole K range and applies the epilogue
+// itself (no partial tiles, no finishing kernel).  (Measured and dropped: a second group of
+// four wavefronts per workgroup that takes half of the K range and hands its accumulators
+// over through LDS, to halve the splits across workgroups: 2-10 % slower per GEMM than more,
+// smaller workgroups plus the finishing kernel.)
+// OWN selects that variant at compile time, so that the variant that writes partial tiles carries
+// none of the epilogue's registers (it runs four wavefronts per SIMD, the other three).
+template <int MT, bool GLU, int EPI, bool OWN>
 __global__ void __launch_bounds__(WAVES * 64)
 k_gemm_wide(const bf16* __restrict__ X, const bf16* __restrict__ W, int M, int N, int K,
-            float* __restrict__ part, int blocks_per_split) {
+            float* __restrict__ part, int blocks_per_split, void* __restrict__ outv, float* __restrict__ resid,
+            SkinnyFusion fu) {
   constexpr int NW = GLU ? 2 : 1;
 #ifndef LS_WIDE_PF
 #define LS_WIDE_PF 2
@@ -35,9 +99,10 @@ k_gemm_wide(const bf16* __restrict__ X, const bf16* __restrict__ W, int M, int N
   constexpr int PF = LS_WIDE_PF;
   constexpr int XS_BYTES = MT * 16 * 256;  // one staged X block
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  unsigned char* xs = smem;                                   // [2][MT*16 rows][256 B]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  unsigned char* xs = smem;                                   // [2][MT*16 rows][256 B]
   unsigned char* scratch = smem + 2 * XS_BYTES + wave * (NW * 4096);
+  float* inv_s = reinterpret_cast<float*>(smem + 2 * XS_BYTES + WAVES * NW * 4096);  // [MT*16]
   const int lr = lane & 15, lg = lane >> 4;
   const int n0 = blockIdx.x * 64 + wave * 16;
   const int nblk = K >> 7;
@@ -93,34 +158,61 @@ k_gemm_wide(const bf16* __restrict__ X, const bf16* __restrict__ W, int M, int N
   // one K step with ring slot `slot`
 #define LS_STEP(slot, b)                                                                        \
   {                                                                                             \
-    if ((b) + 1 < nb) LS_LOAD_X(b0 + (b) + 1)                                                   \
-    _Pragma("unroll") for (int s_ = 0; s_ < NW; ++s_)                                           \
-      _Pragma("unroll") for (int i_ = 0; i_ < 4; ++i_)                                          \
-        *reinterpret_cast<u32x4*>(scratch + s_ * 4096 + i_ * 1024 + lane * 16) = wr[slot][s_][i_]; \
-    if ((b) + PF < nb) LS_LOAD_W(slot, b0 + (b) + PF)                                           \
-    const unsigned char* xb_ = xs + ((b) & 1) * XS_BYTES;                                       \
-    _Pragma("unroll") for (int kk = 0; kk < 4; ++kk) {                                          \
-      bf16x8 xf_[MT];                                                                           \
-      _Pragma("unroll") for (int t = 0; t < MT; ++t)                                            \
-        xf_[t] = *reinterpret_cast<const bf16x8*>(xb_ + (lr + 16 * t) * 256 + (((kk * 4 + lg) ^ lr) << 4)); \
-      _Pragma("unroll") for (int s_ = 0; s_ < NW; ++s_) {                                       \
-        const bf16x8 af_ = *reinterpret_cast<const bf16x8*>(scratch + s_ * 4096 + a_off[kk]);   \
+    {                                                                                           \
+      if ((b) + 1 < nb) LS_LOAD_X(b0 + (b) + 1)                                                 \
+      _Pragma("unroll") for (int s_ = 0; s_ < NW; ++s_)                                         \
+        _Pragma("unroll") for (int i_ = 0; i_ < 4; ++i_)                                        \
+          *reinterpret_cast<u32x4*>(scratch + s_ * 4096 + i_ * 1024 + lane * 16) = wr[slot][s_][i_]; \
+      if ((b) + PF < nb) LS_LOAD_W(slot, b0 + (b) + PF)                                         \
+      const unsigned char* xb_ = xs + ((b) & 1) * XS_BYTES;                                     \
+      _Pragma("unroll") for (int kk = 0; kk < 4; ++kk) {                                        \
+        bf16x8 xf_[MT];                                                                         \
         _Pragma("unroll") for (int t = 0; t < MT; ++t)                                          \
-          acc[s_][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af_, xf_[t], acc[s_][t], 0, 0, 0); \
+          xf_[t] = *reinterpret_cast<const bf16x8*>(xb_ + (lr + 16 * t) * 256 + (((kk * 4 + lg) ^ lr) << 4)); \
+        _Pragma("unroll") for (int s_ = 0; s_ < NW; ++s_) {                                     \
+          const bf16x8 af_ = *reinterpret_cast<const bf16x8*>(scratch + s_ * 4096 + a_off[kk]); \
+          _Pragma("unroll") for (int t = 0; t < MT; ++t)                                        \
+            acc[s_][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af_, xf_[t], acc[s_][t], 0, 0, 0); \
+        }                                                                                       \
       }                                                                                         \
+      if ((b) + 1 < nb) LS_STORE_X(((b) + 1) & 1)                                               \
     }                                                                                           \
-    if ((b) + 1 < nb) LS_STORE_X(((b) + 1) & 1)                                                 \
     __syncthreads();                                                                            \
   }
 
-  if (nb > 0) {
+  if (nb > 0) {  // the same for every wavefront of the workgroup
     LS_LOAD_X(b0)
 #pragma unroll
     for (int p = 0; p < PF; ++p)
       if (p < nb) LS_LOAD_W(p, b0 + p)
     LS_STORE_X(0)
+    if constexpr (OWN) {
+      if (fu.ss_in) {
+        // folded RMSNorm: 1/rms of every row from its partial sums of squares, worked out while
+        // the first weight blocks are on their way.  Wavefront w takes rows w, w + 4, ...; all of
+        // a wavefront's loads are issued before the first reduction (n_part = K/16 is a multiple of 8).
+        constexpr int RPW = (MT * 16 + WAVES - 1) / WAVES;
+        float rs[RPW];
+#pragma unroll
+        for (int r = 0; r < RPW; ++r) {
+          const int m = wave + WAVES * r;
+          rs[r] = 0.f;
+          if (m < M)
+            for (int i = lane * 4; i < fu.n_part; i += 256) {
+              const f32x4 v = *reinterpret_cast<const f32x4*>(fu.ss_in + (size_t)m * fu.n_part + i);
+              rs[r] += (v[0] + v[1]) + (v[2] + v[3]);
+            }
+        }
+#pragma unroll
+        for (int r = 0; r < RPW; ++r) {
+          const int m = wave + WAVES * r;
+          const float ss = wave_sum(rs[r]);
+          if (lane == 0 && m < M) inv_s[m] = 1.0f / sqrtf(ss / (float)K + fu.eps);
+        }
+      }
+    }
     __syncthreads();
-    for (int b = 0; b < nb; b += PF) {  // nb is the same for every wavefront of the workgroup
+    for (int b = 0; b < nb; b += PF) {
 #pragma unroll
       for (int sl = 0; sl < PF; ++sl)
         if (b + sl < nb) LS_STEP(sl, b + sl)
@@ -131,6 +223,13 @@ k_gemm_wide(const bf16* __restrict__ X, const bf16* __restrict__ W, int M, int N
 #undef LS_STORE_X
 #undef LS_STEP
 
+  if constexpr (OWN) {
+    float inv[MT];
+#pragma unroll
+    for (int t = 0; t < MT; ++t) inv[t] = fu.ss_in ? inv_s[min(lr + 16 * t, M - 1)] : 1.f;
+    wide_epilogue<EPI, MT, NW>(acc, inv, M, N, n0 + lg * 4, lr, lg, outv, resid, fu);
+    return;
+  }
   // partial tile of this K split: part[split][stream][m][N]
 #pragma unroll
   for (int s = 0; s < NW; ++s)
@@ -217,20 +316,24 @@ k_wide_finish(const float* __restrict__ part, int splits, int M, int N, int K, v
   }
 }
 
-template <int MT, bool GLU>
-void launch_main(const void* X, const void* W, int M, int N, int K, float* part, int splits, int bps, hipStream_t st) {
+template <int MT, int EPI>
+void launch_main(const void* X, const void* W, int M, int N, int K, float* part, int splits, int bps, void* out,
+                 float* resid, const SkinnyFusion& fu, hipStream_t st) {
+  constexpr bool GLU = EPI == EPI_SWIGLU;
   constexpr int NW = GLU ? 2 : 1;
-  constexpr int smem = 2 * MT * 16 * 256 + WAVES * NW * 4096;
-  static std::atomic<uint64_t> lds_allowed{0};
-  allow_dynamic_lds((const void*)k_gemm_wide<MT, GLU>, smem, lds_allowed);
+  constexpr int smem = 2 * MT * 16 * 256 + WAVES * NW * 4096 + MT * 16 * 4;
+  constexpr int EPI_PART = GLU ? EPI_SWIGLU : EPI_STORE;  // the partial-tile variant has no epilogue: one per GLU
+  static std::atomic<uint64_t> lds_own{0}, lds_part{0};
   dim3 grid(N / 64, splits);
-  k_gemm_wide<MT, GLU><<<grid, WAVES * 64, smem, st>>>((const bf16*)X, (const bf16*)W, M, N, K, part, bps);
-}
-
-template <bool GLU>
-void launch_mt(const void* X, const void* W, int M, int N, int K, float* part, int splits, int bps, hipStream_t st) {
-  if (M <= 32) launch_main<2, GLU>(X, W, M, N, K, part, splits, bps, st);
-  else launch_main<4, GLU>(X, W, M, N, K, part, splits, bps, st);
+  if (splits == 1) {  // the whole operator is this one kernel: it may carry the runtime's start/stop events
+    allow_dynamic_lds((const void*)k_gemm_wide<MT, GLU, EPI, true>, smem, lds_own);
+    launch_kernel(k_gemm_wide<MT, GLU, EPI, true>, grid, dim3(WAVES * 64), smem, st, (const bf16*)X, (const bf16*)W, M, N,
+                  K, part, bps, out, resid, fu);
+  } else {
+    allow_dynamic_lds((const void*)k_gemm_wide<MT, GLU, EPI_PART, false>, smem, lds_part);
+    hipLaunchKernelGGL((k_gemm_wide<MT, GLU, EPI_PART, false>), grid, dim3(WAVES * 64), smem, st, (const bf16*)X,
+                       (const bf16*)W, M, N, K, part, bps, out, resid, fu);
+  }
 }
 
 template <int EPI>
@@ -239,6 +342,16 @@ void launch_finish(const float* part, int splits, int M, int N, int K, void* out
   dim3 grid((N + 1023) / 1024, M);
   if (fu.ss_in) k_wide_finish<EPI, true><<<grid, 256, 0, st>>>(part, splits, M, N, K, out, resid, fu);
   else k_wide_finish<EPI, false><<<grid, 256, 0, st>>>(part, splits, M, N, K, out, resid, fu);
+}
+
+template <int EPI>
+void launch_epi(const void* X, const void* W, int M, int N, int K, void* out, float* resid, float* splitk_ws,
+                hipStream_t st, const SkinnyFusion& fu) {
+  const int splits = gemm_wide_splits(N, K);
+  const int nblk = K / 128, bps = (nblk + splits - 1) / splits;
+  if (M <= 32) launch_main<2, EPI>(X, W, M, N, K, splitk_ws, splits, bps, out, resid, fu, st);
+  else launch_main<4, EPI>(X, W, M, N, K, splitk_ws, splits, bps, out, resid, fu, st);
+  if (splits > 1) launch_finish<EPI>(splitk_ws, splits, M, N, K, out, resid, fu, st);
 }
 
 }  // namespace
@@ -259,21 +372,18 @@ bool gemm_wide_supported(int M, int N, int K) {
 }
 
 size_t gemm_wide_workspace_bytes(int M, int N, int K, bool glu) {
-  return (size_t)gemm_wide_splits(N, K) * (glu ? 2 : 1) * M * N * sizeof(float);
+  const int splits = gemm_wide_splits(N, K);
+  return splits > 1 ? (size_t)splits * (glu ? 2 : 1) * M * N * sizeof(float) : 0;
 }
 
 void launch_gemm_wide(Epilogue epi, const void* X, const void* W, int M, int N, int K, void* out, float* resid,
                       float* splitk_ws, hipStream_t st, const SkinnyFusion* fusion) {
   const SkinnyFusion fu = fusion ? *fusion : SkinnyFusion{};
-  const int splits = gemm_wide_splits(N, K);
-  const int nblk = K / 128, bps = (nblk + splits - 1) / splits;
-  if (epi == EPI_SWIGLU) launch_mt<true>(X, W, M, N, K, splitk_ws, splits, bps, st);
-  else launch_mt<false>(X, W, M, N, K, splitk_ws, splits, bps, st);
   switch (epi) {
-    case EPI_STORE: launch_finish<EPI_STORE>(splitk_ws, splits, M, N, K, out, resid, fu, st); break;
-    case EPI_RESID: launch_finish<EPI_RESID>(splitk_ws, splits, M, N, K, out, resid, fu, st); break;
-    case EPI_SWIGLU: launch_finish<EPI_SWIGLU>(splitk_ws, splits, M, N, K, out, resid, fu, st); break;
-    case EPI_F32: launch_finish<EPI_F32>(splitk_ws, splits, M, N, K, out, resid, fu, st); break;
+    case EPI_STORE: launch_epi<EPI_STORE>(X, W, M, N, K, out, resid, splitk_ws, st, fu); break;
+    case EPI_RESID: launch_epi<EPI_RESID>(X, W, M, N, K, out, resid, splitk_ws, st, fu); break;
+    case EPI_SWIGLU: launch_epi<EPI_SWIGLU>(X, W, M, N, K, out, resid, splitk_ws, st, fu); break;
+    case EPI_F32: launch_epi<EPI_F32>(X, W, M, N, K, out, resid, splitk_ws, st, fu); break;
   }
 }
 

@@ -57,8 +57,9 @@ def test_static_scratch_decode_refuses_a_step_that_does_not_fit():
     import torch
     from paper_2502_09922_amd import LsError, binding as b
 
-    # 64 rows x (gate + up) x 20480 columns x 4 bytes = 10 MiB per K split, 2 splits: beyond 16 MiB
-    big = synth.StageShape("bf16", 1, 1024, 8, 8, 128, 20480, 0)
+    # the 7B layer shape at 64 rows: the gate/up projection is cut into 4 K ranges across
+    # workgroups, 4 x (gate + up) x 64 rows x 11008 columns x 4 bytes = 21.5 MiB: beyond 16 MiB
+    big = synth.StageShape("bf16", 1, 4096, 32, 32, 128, 11008, 0)
     st = make_gpu(big, 3, 0, 1, 64, 8, 64)
     x = to_dev(big, synth.hidden_states(big, 4, 64))
     st.prefill(x, [1] * 64)
