@@ -147,7 +147,7 @@ def stats(v):
     return {"mean": float(np.mean(v)), "median": float(np.median(v)), "min": float(v[0])}
 
 
-def run_throughput(name, steps, warmup, probes=True, peaks=False):
+def run_throughput(name, steps, warmup, probes=True, peaks=False, decode_steps=None):
     """Time `steps` steps of workload `name` (after `warmup`), weights resident.  Returns the
     per-phase numbers and, if asked, the live per-kernel probes."""
     import torch
@@ -156,6 +156,8 @@ def run_throughput(name, steps, warmup, probes=True, peaks=False):
     from paper_2502_09922_amd import Stage, binding as B
 
     key, lo, hi, batch, prompt, dsteps = WORKLOADS[name]
+    if decode_steps is not None:
+        dsteps = decode_steps
     shape = synth.CONFIGS[key]
     if not (lo == 0 and hi == shape.n_layers_total):
         shape = shape.with_(vocab=0) if not (lo == 0 or hi == shape.n_layers_total) else shape
@@ -189,6 +191,7 @@ def run_throughput(name, steps, warmup, probes=True, peaks=False):
     ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
     mid_layer = (lo + hi) // 2
     PROBED = min(16, dsteps)  # decode steps per step whose gate-up launch is probed
+    probes = probes and dsteps > 0
     probe_lo = (dsteps - PROBED) // 2
     probe_hi = probe_lo + PROBED
 
@@ -242,9 +245,9 @@ def run_throughput(name, steps, warmup, probes=True, peaks=False):
                     "tokens_per_s": T / (pre["mean"] * 1e-3), "tflops": pre_flops / (pre["mean"] * 1e-3) / 1e12,
                     "frac_of_bf16_mfma_peak": pre_flops / (pre["mean"] * 1e-3) / 1e12 / MFMA_BF16_PEAK_TF},
         "decode": {"ms": dec["mean"], "ms_median": dec["median"], "ms_min": dec["min"],
-                   "ms_per_token_step": dec["mean"] / dsteps, "tokens_per_s": batch * dsteps / (dec["mean"] * 1e-3),
-                   "gbytes_per_s": dec_bytes / (dec["mean"] * 1e-3) / 1e9,
-                   "frac_of_hbm_peak": dec_bytes / (dec["mean"] * 1e-3) / 1e9 / HBM_PEAK_GBS},
+                   "ms_per_token_step": dec["mean"] / max(dsteps, 1), "tokens_per_s": batch * dsteps / max(dec["mean"] * 1e-3, 1e-9),
+                   "gbytes_per_s": dec_bytes / max(dec["mean"] * 1e-3, 1e-9) / 1e9,
+                   "frac_of_hbm_peak": dec_bytes / max(dec["mean"] * 1e-3, 1e-9) / 1e9 / HBM_PEAK_GBS},
     })
     if peaks:
         out["prefill"]["frac_of_measured_mfma_rate"] = out["prefill"]["tflops"] / out["measured_peaks"]["mfma_bf16_tflops"]
@@ -449,6 +452,8 @@ def main():
     ap.add_argument("--workload", default=DEFAULT, choices=sorted(WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the other configurations (other_workloads, execute_while_load)")
+    ap.add_argument("--decode-steps", type=int, default=None,
+                    help="override the workload's number of decode steps (0: prompt pass only; for profiler runs)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain 1 GiB device copy (calibrates rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -476,8 +481,15 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    main_run, shape, lengths = run_throughput(args.workload, args.steps, args.warmup, probes=True, peaks=True)
+    main_run, shape, lengths = run_throughput(args.workload, args.steps, args.warmup, probes=True, peaks=True,
+                                              decode_steps=args.decode_steps)
     key, lo, hi, batch, prompt, dsteps = WORKLOADS[args.workload]
+    if args.decode_steps is not None:
+        dsteps = args.decode_steps
+    if dsteps == 0:  # a profiler run of the prompt pass alone: phase numbers only
+        print(json.dumps({"metric": "stage prefill tokens/s (1 GPU), prompt pass only", "value": main_run["prefill"]["tokens_per_s"],
+                          "unit": "tokens/s", "config": {"workload": args.workload, "decode_steps": 0}, "prefill": main_run["prefill"]}))
+        return
     pg, dg = main_run.pop("probe_prefill_gateup"), main_run.pop("probe_decode_gateup")
     # the kernel that takes the largest share of the step is the one `roofline` reports
     prefill_dominant = pg["share_of_step"] >= dg["share_of_step"]

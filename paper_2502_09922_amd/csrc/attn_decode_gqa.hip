@@ -5,8 +5,17 @@
 // are small matrix products and run on the matrix cores; the vector ALUs only do the softmax.
 // The kernel stays bound by streaming the cache out of HBM once per step.
 //
-//   * One workgroup per (sequence, kv head); its NW wavefronts split the keys 0..pos into
-//     contiguous runs of 32-key tiles (split-KV inside the workgroup, merged in wave order).
+//   * One workgroup per (sequence, kv head, chunk of 2048 keys); its NW wavefronts split the
+//     chunk's 32-key tiles into contiguous runs (split-KV inside the workgroup, merged in wave
+//     order).  A sequence of up to 2048 keys is one workgroup, which writes the output row; a
+//     longer one is several workgroups, each of which leaves its running maximum, its sum and
+//     its un-normalised output in a scratch buffer, and a small second kernel adds them up in
+//     chunk order (a fixed order: the result does not depend on timing).  Measured at the 70B
+//     shape (64 ragged contexts of 128..2300 keys, 8 kv heads): chunks of 512 keys make the
+//     kernel 24 % slower, 1024 keys 11 %, 2048 keys change nothing -- a workgroup's start
+//     (query rotation, first tile) and end (merge through LDS) cost several microseconds, more
+//     than the ragged batch loses by waiting for its longest sequence; the chunks are there for
+//     contexts of many thousands of keys, where one workgroup per sequence would leave the chip idle.
 //   * A tile (32 keys x 256 bytes of K, the same of V) is fetched with sixteen 16-byte-per-lane
 //     non-temporal loads, a quarter-wave per cache row (whole rows, 1 KB per instruction), and
 //     goes through a wave-private LDS area (written lane-linear; the 16-byte chunks of a row
@@ -18,7 +27,9 @@
 //     the running maximum and sum are per-lane values plus an exchange with lanes +-16, +-32.
 //   * O^T[d][head] += V^T P^T: the eight probabilities a lane holds for a tile are exactly a
 //     B operand whose k index runs over keys {4g..4g+3, 16+4g..16+4g+3} (g = lane/16); the V^T
-//     operand gathers the same keys for its row d from the row-major V tile in LDS.
+//     operand for row d comes out of two transposing LDS reads (ds_read_b64_tr_b16) of the
+//     row-major V tile: the 16 lanes of group g address a block of 4 keys x 16 dims (lane j:
+//     key j/4, dims 4(j%4)..+3) and lane j receives the four keys' values at dim j.
 //   * The new row: its key is rotated and rounded to bf16, appended to the cache together
 //     with the value, and patched into the LDS tile that covers position `pos`, so it takes
 //     the same path as every cached key.  Cache rows past `pos` are never used: keys are
@@ -33,17 +44,24 @@ namespace {
 constexpr int HD = 128;
 constexpr int TK = 32;                   // keys per tile
 constexpr int TILE_BYTES = TK * HD * 2;  // 8 KB of K, 8 KB of V
+#ifndef LS_GQA_TPC
+#define LS_GQA_TPC 64
+#endif
+constexpr int TPC = LS_GQA_TPC;          // tiles per chunk: 2048 keys (one chunk per sequence without scratch)
+constexpr int PART_HDR = 32;             // floats in front of a partial result: 16 maxima, 16 sums
 
 template <int NW>
 __global__ void __launch_bounds__(NW * 64)
 k_attn_decode_gqa(const bf16* __restrict__ qkv, int qkv_stride, const float2* __restrict__ cs,
                   bf16* __restrict__ kc, bf16* __restrict__ vc, const int32_t* __restrict__ row_seq,
-                  const int32_t* __restrict__ row_pos, int hq, int hkv, int G, int max_seq, bf16* __restrict__ out) {
+                  const int32_t* __restrict__ row_pos, int hq, int hkv, int G, int max_seq, bf16* __restrict__ out,
+                  float* __restrict__ part, int nchunk, int tpc) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const int r = blockIdx.x, kh = blockIdx.y;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int pos = row_pos[r];
   if (pos < 0) return;  // a sequence with no room left: whole workgroup leaves together
+  if ((int)blockIdx.z * tpc * TK > pos) return;  // this chunk lies beyond the sequence's context
   const int seq = row_seq[r];
   const int lr = lane & 15, lg = lane >> 4;
   bf16* kb = kc + ((size_t)seq * hkv + kh) * max_seq * HD;
@@ -51,6 +69,39 @@ k_attn_decode_gqa(const bf16* __restrict__ qkv, int qkv_stride, const float2* __
   const bf16* row = qkv + (size_t)r * qkv_stride;
   unsigned char* ks = smem + wave * (2 * TILE_BYTES);
   unsigned char* vs = ks + TILE_BYTES;
+
+  // tiles of this workgroup's chunk of the ceil((pos+1)/32) tiles, and of this wave: a contiguous run
+  const int ntile = (pos + TK) / TK;
+  const int t_lo = blockIdx.z * tpc;
+  // the last chunk takes whatever is left, should the caller have understated the longest context
+  const int t_hi = (int)blockIdx.z == nchunk - 1 ? ntile : min(t_lo + tpc, ntile);
+  const int per = (t_hi - t_lo + NW - 1) / NW;
+  const int t_begin = min(t_lo + wave * per, t_hi), t_end = min(t_begin + per, t_hi);
+
+  // per-lane load coordinates inside a tile: instruction i fetches key 4i + lg; the lane
+  // lands in physical chunk lr and therefore fetches the logical chunk that belongs there
+  int kchunk[8], vchunk[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const int kl = 4 * i + lg;
+    kchunk[i] = lr ^ (kl & 15);
+    vchunk[i] = lr ^ ((kl & 7) << 1);
+  }
+  u32x4 kreg[8], vreg[8];
+#define LS_LOAD_TILE(t)                                                                                  \
+  _Pragma("unroll") for (int i = 0; i < 8; ++i) {                                                        \
+    const int key_ = min((t) * TK + 4 * i + lg, max(pos - 1, 0)); /* a row the cache already holds */    \
+    kreg[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(kb + (size_t)key_ * HD + kchunk[i] * 8)); \
+    vreg[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(vb + (size_t)key_ * HD + vchunk[i] * 8)); \
+  }
+
+  f32x4 o[8];
+#pragma unroll
+  for (int dt = 0; dt < 8; ++dt) o[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+  float m_run = -INFINITY, l_run = 0.f;                       // l_run: this lane group's share of the sum
+  const float c = 1.4426950408889634f / sqrtf((float)HD);      // scores are kept in log2 units
+
+  if (t_begin < t_end) LS_LOAD_TILE(t_begin)  // on its way while the query operand is prepared
 
   // query operand: head lr (zero beyond G), dims kk*32 + 8*lg .. +7, rotated at `pos`
   bf16x8 qf[4];
@@ -73,35 +124,6 @@ k_attn_decode_gqa(const bf16* __restrict__ qkv, int qkv_stride, const float2* __
     qf[kk] = qv;
   }
 
-  // tiles of this wave: a contiguous run of the ceil((pos+1)/32) tiles
-  const int ntile = (pos + TK) / TK;
-  const int per = (ntile + NW - 1) / NW;
-  const int t_begin = min(wave * per, ntile), t_end = min(t_begin + per, ntile);
-
-  // per-lane load coordinates inside a tile: instruction i fetches key 4i + lg; the lane
-  // lands in physical chunk lr and therefore fetches the logical chunk that belongs there
-  int kchunk[8], vchunk[8];
-#pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    const int kl = 4 * i + lg;
-    kchunk[i] = lr ^ (kl & 15);
-    vchunk[i] = lr ^ (((kl >> 2) & 3) << 2);
-  }
-  u32x4 kreg[8], vreg[8];
-#define LS_LOAD_TILE(t)                                                                                  \
-  _Pragma("unroll") for (int i = 0; i < 8; ++i) {                                                        \
-    const int key_ = min((t) * TK + 4 * i + lg, max(pos - 1, 0)); /* a row the cache already holds */    \
-    kreg[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(kb + (size_t)key_ * HD + kchunk[i] * 8)); \
-    vreg[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(vb + (size_t)key_ * HD + vchunk[i] * 8)); \
-  }
-
-  f32x4 o[8];
-#pragma unroll
-  for (int dt = 0; dt < 8; ++dt) o[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
-  float m_run = -INFINITY, l_run = 0.f;                       // l_run: this lane group's share of the sum
-  const float c = 1.4426950408889634f / sqrtf((float)HD);      // scores are kept in log2 units
-
-  if (t_begin < t_end) LS_LOAD_TILE(t_begin)
   for (int t = t_begin; t < t_end; ++t) {
     const int key0 = t * TK;
     // registers -> LDS; values of keys past `pos` are zeroed (their probabilities are zero, but
@@ -126,7 +148,7 @@ k_attn_decode_gqa(const bf16* __restrict__ qkv, int qkv_stride, const float2* __
         kr[2 * i + 1] = (bf16)(u0 * tt.y + u1 * tt.x);
       }
       *reinterpret_cast<bf16x8*>(ks + kl * 256 + ((lane ^ (kl & 15)) << 4)) = kr;
-      *reinterpret_cast<bf16x8*>(vs + kl * 256 + ((lane ^ (((kl >> 2) & 3) << 2)) << 4)) = vn;
+      *reinterpret_cast<bf16x8*>(vs + kl * 256 + ((lane ^ ((kl & 7) << 1)) << 4)) = vn;
       *reinterpret_cast<bf16x8*>(kb + (size_t)pos * HD + lane * 8) = kr;
       *reinterpret_cast<bf16x8*>(vb + (size_t)pos * HD + lane * 8) = vn;
     }
@@ -172,19 +194,26 @@ k_attn_decode_gqa(const bf16* __restrict__ qkv, int qkv_stride, const float2* __
     l_run = l_run * corr + psum;
     m_run = m_new;
     // ---- O^T = O^T * corr + V^T P^T
+    // transposing reads: group lg hands in keys 4 lg + j/4 (and 16 more for the second half),
+    // dims 16 dt + 4 (j%4); the chunk swizzle (key & 7) << 1 spreads the 4 keys x 32 bytes of
+    // the four groups over all banks twice
+    {
+      typedef short s16x4 __attribute__((ext_vector_type(4)));
+      typedef short s16x8 __attribute__((ext_vector_type(8)));
+      typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+      const int k0 = 4 * lg + (lr >> 2), k1 = k0 + 16;
+      const int sw0 = (k0 & 7) << 1, sw1 = (k1 & 7) << 1;
+      const int sub = (lr & 1) * 8;  // dims 4 (j%4): chunk (j%4)/2 of the 16 dims, half (j%4)&1
 #pragma unroll
-    for (int dt = 0; dt < 8; ++dt) {
-      const int d = dt * 16 + lr;
-      const int chunk = ((d >> 3) ^ (lg << 2)) << 4;  // keys 4g+e and 16+4g+e share the swizzle term g
-      bf16x8 vf;
+      for (int dt = 0; dt < 8; ++dt) {
+        const int ch = dt * 2 + ((lr & 3) >> 1);
+        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(vs + k0 * 256 + ((ch ^ sw0) << 4) + sub));
+        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(vs + k1 * 256 + ((ch ^ sw1) << 4) + sub));
+        const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
 #pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        const int kl = 16 * (j >> 2) + 4 * lg + (j & 3);
-        vf[j] = *reinterpret_cast<const bf16*>(vs + kl * 256 + chunk + (d & 7) * 2);
+        for (int e = 0; e < 4; ++e) o[dt][e] *= corr;
+        o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, both), pf, o[dt], 0, 0, 0);
       }
-#pragma unroll
-      for (int e = 0; e < 4; ++e) o[dt][e] *= corr;
-      o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf, o[dt], 0, 0, 0);
     }
   }
 #undef LS_LOAD_TILE
@@ -202,6 +231,8 @@ k_attn_decode_gqa(const bf16* __restrict__ qkv, int qkv_stride, const float2* __
   for (int dt = 0; dt < 8; ++dt)
     *reinterpret_cast<f32x4*>(sm_o + ((wave * 16 + lr) * HD + dt * 16 + 4 * lg)) = o[dt];
   __syncthreads();
+  const bool whole = ntile <= tpc || nchunk == 1;  // the sequence is this one chunk: write its output row
+  float* pp = part + (((size_t)r * hkv + kh) * nchunk + blockIdx.z) * (PART_HDR + (size_t)G * HD);
   for (int i = threadIdx.x; i < G * HD; i += NW * 64) {
     const int g = i / HD, d = i % HD;
     float mm = -INFINITY;
@@ -215,19 +246,54 @@ k_attn_decode_gqa(const bf16* __restrict__ qkv, int qkv_stride, const float2* __
       num += sm_o[(w * 16 + g) * HD + d] * wt;
       den += sm_l[w * 16 + g] * wt;
     }
+    if (whole) {
+      out[(size_t)r * ((size_t)hq * HD) + (size_t)(kh * G + g) * HD + d] = (bf16)(num / den);
+    } else {
+      pp[PART_HDR + i] = num;
+      if (d == 0) { pp[g] = mm; pp[16 + g] = den; }
+    }
+  }
+}
+
+// Second pass for sequences longer than one chunk: the chunks' partial results in chunk order.
+__global__ void __launch_bounds__(256)
+k_attn_gqa_merge(const float* __restrict__ part, const int32_t* __restrict__ row_pos, int hq, int hkv, int G, int nchunk,
+                 int tpc, bf16* __restrict__ out) {
+  const int r = blockIdx.x, kh = blockIdx.y;
+  const int pos = row_pos[r];
+  if (pos < 0) return;
+  const int ntile = (pos + TK) / TK;
+  if (ntile <= tpc) return;  // the first pass wrote this row
+  const int nch = min((ntile + tpc - 1) / tpc, nchunk);
+  const size_t stride = PART_HDR + (size_t)G * HD;
+  const float* p0 = part + ((size_t)r * hkv + kh) * nchunk * stride;
+  for (int i = threadIdx.x; i < G * HD; i += 256) {
+    const int g = i / HD, d = i % HD;
+    float mm = -INFINITY;
+    for (int c = 0; c < nch; ++c) mm = fmaxf(mm, p0[c * stride + g]);
+    float num = 0.f, den = 0.f;
+    for (int c = 0; c < nch; ++c) {
+      const float wt = __builtin_amdgcn_exp2f(p0[c * stride + g] - mm);  // every chunk holds a visible key: finite
+      num += p0[c * stride + PART_HDR + i] * wt;
+      den += p0[c * stride + 16 + g] * wt;
+    }
     out[(size_t)r * ((size_t)hq * HD) + (size_t)(kh * G + g) * HD + d] = (bf16)(num / den);
   }
 }
 
 template <int NW>
 void launch_nw(const void* qkv, int qkv_stride, const float* cs, void* kc, void* vc, const int32_t* row_seq,
-               const int32_t* row_pos, int rows, int hq, int hkv, int max_seq, void* out, hipStream_t st) {
+               const int32_t* row_pos, int rows, int hq, int hkv, int max_seq, void* out, hipStream_t st, float* part,
+               int nchunk, int tpc) {
   constexpr int SMEM = NW * 2 * TILE_BYTES;  // >= the merge area: NW * (32 + 16*128) floats
   static std::atomic<uint64_t> lds_allowed{0};
   allow_dynamic_lds((const void*)k_attn_decode_gqa<NW>, SMEM, lds_allowed);
-  dim3 grid(rows, hkv);
+  dim3 grid(rows, hkv, nchunk);
   k_attn_decode_gqa<NW><<<grid, NW * 64, SMEM, st>>>((const bf16*)qkv, qkv_stride, (const float2*)cs, (bf16*)kc,
-                                                     (bf16*)vc, row_seq, row_pos, hq, hkv, hq / hkv, max_seq, (bf16*)out);
+                                                     (bf16*)vc, row_seq, row_pos, hq, hkv, hq / hkv, max_seq, (bf16*)out,
+                                                     part, nchunk, tpc);
+  if (nchunk > 1)
+    k_attn_gqa_merge<<<dim3(rows, hkv), 256, 0, st>>>(part, row_pos, hq, hkv, hq / hkv, nchunk, tpc, (bf16*)out);
 }
 
 }  // namespace
@@ -240,11 +306,27 @@ bool attn_decode_gqa_supported(int hq, int hkv, int hd) {
 #ifndef LS_ATTN_GQA_NW
 #define LS_ATTN_GQA_NW 4
 #endif
+size_t attn_decode_gqa_scratch_bytes(int rows, int hq, int hkv, int max_keys) {
+  if (!attn_decode_gqa_supported(hq, hkv, HD)) return 0;
+  const int nchunk = ((max_keys + TK - 1) / TK + TPC - 1) / TPC;
+  if (nchunk <= 1) return 0;
+  return (size_t)rows * hkv * nchunk * (PART_HDR + (size_t)(hq / hkv) * HD) * sizeof(float);
+}
+
 void launch_attn_decode_gqa(const void* qkv, int qkv_stride, const float* cs_table, void* kc, void* vc,
                             const int32_t* row_seq, const int32_t* row_pos, int rows, int hq, int hkv, int max_seq,
-                            void* out, hipStream_t st) {
+                            void* out, hipStream_t st, int max_keys, float* scratch, size_t scratch_bytes) {
   if (rows <= 0) return;
-  launch_nw<LS_ATTN_GQA_NW>(qkv, qkv_stride, cs_table, kc, vc, row_seq, row_pos, rows, hq, hkv, max_seq, out, st);
+  // chunks of TPC tiles up to the longest context the caller vouches for; without scratch for
+  // their partial results every sequence stays one workgroup (one chunk as long as the cache)
+  const int tiles = (min(max(max_keys, 1), max_seq) + TK - 1) / TK;
+  int tpc = TPC, nchunk = (tiles + TPC - 1) / TPC;
+  if (nchunk > 1 && (!scratch || attn_decode_gqa_scratch_bytes(rows, hq, hkv, max_keys) > scratch_bytes)) {
+    tpc = (max_seq + TK - 1) / TK;
+    nchunk = 1;
+  }
+  launch_nw<LS_ATTN_GQA_NW>(qkv, qkv_stride, cs_table, kc, vc, row_seq, row_pos, rows, hq, hkv, max_seq, out, st, scratch,
+                            nchunk, tpc);
 }
 
 }  // namespace ls

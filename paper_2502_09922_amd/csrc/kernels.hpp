@@ -119,13 +119,15 @@ void launch_rope_append(uint32_t dt, void* qkv, const float* cs_table, const int
 // q is read from qkv ([rows, qkv_stride]); out is [rows, Hq*hd].
 // Attention of one layer, including RoPE and the KV-cache append of the call's rows.
 // qkv [rows, (Hq+2Hkv)*hd] holds the un-rotated projections and may be rotated in place.
-// Decode (cu_seqlens == nullptr): every row is the single new row of its sequence.
+// Decode (cu_seqlens == nullptr): every row is the single new row of its sequence; max_len is
+// then an upper bound of the keys a row attends to, and attn_scratch the buffer for the
+// partial results of contexts that are split over several workgroups (may be nullptr).
 // Prefill: sequence b owns rows [cu_seqlens[b], cu_seqlens[b+1]) at positions 0.., the
 // longest sequence has max_len rows.  out is [rows, Hq*hd].
 void launch_attention_block(uint32_t dt, const int32_t* cu_seqlens, int batch, int max_len, void* qkv,
                             const float* cs_table, void* kcache, void* vcache, const int32_t* row_seq,
                             const int32_t* row_pos, int rows, int hq, int hkv, int hd, int max_seq, void* out,
-                            hipStream_t st);
+                            hipStream_t st, float* attn_scratch = nullptr, size_t attn_scratch_bytes = 0);
 
 // bf16 split-KV decode attention fused with RoPE and the cache append; head_dim 64 or 128,
 // Hq/Hkv in {1,2,4,8}.
@@ -137,9 +139,14 @@ void launch_attn_decode(const void* qkv, int qkv_stride, const float* cs_table, 
 // bf16 decode attention on the matrix cores for grouped-query models (head_dim 128,
 // 2 <= Hq/Hkv <= 16), fused with RoPE and the cache append like launch_attn_decode.
 bool attn_decode_gqa_supported(int hq, int hkv, int hd);
+// max_keys: an upper bound of the keys any row attends to in this step (cached + the new one);
+// contexts longer than 512 keys are cut into chunks that run as workgroups of their own and
+// leave partial results in `scratch` (attn_decode_gqa_scratch_bytes; none: one workgroup per
+// sequence and kv head whatever its length).
+size_t attn_decode_gqa_scratch_bytes(int rows, int hq, int hkv, int max_keys);
 void launch_attn_decode_gqa(const void* qkv, int qkv_stride, const float* cs_table, void* kc, void* vc,
                             const int32_t* row_seq, const int32_t* row_pos, int rows, int hq, int hkv, int max_seq,
-                            void* out, hipStream_t st);
+                            void* out, hipStream_t st, int max_keys, float* scratch, size_t scratch_bytes);
 
 // bf16 flash-style causal attention for the prompt pass; head_dim 64 or 128.
 bool attn_prefill_supported(int hq, int hkv, int hd);

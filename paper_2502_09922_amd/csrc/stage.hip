@@ -132,7 +132,8 @@ bool span_ok(const ls_cfg* c, int lo, int hi) {
 
 // ---- workspace carving ------------------------------------------------------------------
 struct Carve {
-  size_t cs, x, y, qkv, attn, h, logits, row_seq, row_pos, last_rows, next_tok, xb, xb2, ss_a, ss_b, splitk, splitk_bytes, total;
+  size_t cs, x, y, qkv, attn, h, logits, row_seq, row_pos, last_rows, next_tok, xb, xb2, ss_a, ss_b, splitk, splitk_bytes,
+      attn_part, attn_part_bytes, total;
 };
 
 Carve carve(const ls_cfg* c, int lo, int hi) {
@@ -166,6 +167,11 @@ Carve carve(const ls_cfg* c, int lo, int hi) {
     w.splitk_bytes = (c->dtype == LS_DTYPE_BF16 && B > 16) ? ls::gemm_scratch_bytes((int)B, cols) : 0;
     w.splitk = take(w.splitk_bytes);
   }
+  // partial results of the grouped-query decode attention for contexts split over workgroups
+  w.attn_part_bytes = c->dtype == LS_DTYPE_BF16
+                          ? ls::attn_decode_gqa_scratch_bytes((int)B, (int)c->n_q_heads, (int)c->n_kv_heads, (int)c->max_seq)
+                          : 0;
+  w.attn_part = take(w.attn_part_bytes);
   (void)lo;
   w.total = off;
   return w;
@@ -586,8 +592,10 @@ ls_status forward(ls_stage* s, bool prefill, const void* in, const int32_t* cu_d
       f_dn.xb_out = (!more && !s->last) ? (__bf16*)out : xb; f_dn.ss_out = ss_a;
       f_dn.gamma_out = more ? gain(li + 1, 0) : nullptr;
       PROBE(LS_OP_GEMM_QKV, launch_gemm(dt, EPI_STORE, xb, base + sp[1].off, rows, qkv_cols, d, qkv, nullptr, st, &gsc, &f_qkv));
-      PROBE(LS_OP_ATTENTION, launch_attention_block(dt, nullptr, batch, 1, qkv, cs, kc, vc, row_seq, row_pos, rows, hq,
-                                                    hkv, hd, c.max_seq, attn, st));
+      PROBE(LS_OP_ATTENTION, launch_attention_block(dt, nullptr, batch, max_len, qkv, cs, kc, vc, row_seq, row_pos, rows,
+                                                    hq, hkv, hd, c.max_seq, attn, st,
+                                                    s->w.attn_part_bytes ? (float*)(ws + s->w.attn_part) : nullptr,
+                                                    s->w.attn_part_bytes));
       PROBE(LS_OP_GEMM_O, launch_gemm(dt, EPI_RESID, attn, base + sp[2].off, rows, d, hq * hd, nullptr, x, st, &gsc, &f_o));
       PROBE(LS_OP_GEMM_GATEUP, launch_gemm(dt, EPI_SWIGLU, xb2, base + sp[4].off, rows, F, d, hbuf, nullptr, st, &gsc, &f_gu));
       if (more) LS_HIP(gate(s->blocks[s->layer0 + li + 1], st));  // its gain is read next
@@ -770,7 +778,8 @@ ls_status ls_stage_decode(ls_stage* s, const void* in, int batch, int max_ctx, c
   if (rc != LS_OK) return rc;
   rc = check_decode("ls_stage_decode", s, batch, max_ctx);
   if (rc != LS_OK) return rc;
-  return forward(s, false, in, nullptr, batch, batch, 1, kv, out, logits_out, (hipStream_t)hip_stream,
+  // max_len of a decode step: the keys a row may attend to (cached ones plus its own)
+  return forward(s, false, in, nullptr, batch, batch, max_ctx + 1, kv, out, logits_out, (hipStream_t)hip_stream,
                  workspace_scratch(s));
 }
 
@@ -792,7 +801,7 @@ ls_status ls_stage_decode_static(ls_stage* s, const void* in, int batch, int max
   ls::GemmScratch g;
   g.splitk = (float*)s->static_scratch;
   g.bytes = LS_STATIC_SCRATCH_BYTES;
-  return forward(s, false, in, nullptr, batch, batch, 1, kv, out, logits_out, (hipStream_t)hip_stream, g);
+  return forward(s, false, in, nullptr, batch, batch, max_ctx + 1, kv, out, logits_out, (hipStream_t)hip_stream, g);
 }
 
 ls_status ls_stage_layer_times(ls_stage* s, float* copy_ms, float* compute_ms, float* copy_end_ms,

@@ -91,6 +91,28 @@ def test_middle_stage_hidden_parity_and_decode(shape, lengths):
     gpu.close()
 
 
+def test_grouped_query_decode_with_contexts_of_128_and_2048_in_one_batch():
+    """Decode attention of a grouped-query model cuts contexts beyond 512 keys into chunks that
+    run as workgroups of their own and are merged in a second pass: short and long contexts in
+    one batch, lengths on both sides of the chunk and tile edges, several steps."""
+    shape = synth.StageShape("bf16", 2, 512, 8, 2, 128, 704, 0)
+    seed, steps = 47, 3
+    lengths = [128, 2048, 511, 512, 513, 1024, 1025, 31, 1535]
+    B, S = len(lengths), max(lengths)
+    gpu = make_gpu(shape, seed, 0, 2, B, S + steps + 1, sum(lengths))
+    ora = make_oracle(shape, seed, 0, 2, B, S + steps + 1)
+    x = synth.hidden_states(shape, seed + 1, sum(lengths))
+    check_close(to_host(gpu.prefill(to_dev(shape, x), lengths)), ora.prefill(x, lengths), "bf16", "GQA ragged prompt")
+    for t in range(steps):
+        xs = synth.hidden_states(shape, seed + 2 + t, B)
+        check_close(to_host(gpu.decode(to_dev(shape, xs), B, S + t)), ora.decode(xs), "bf16", "GQA ragged step %d" % t)
+    # a caller that understates the longest context still gets every key attended to
+    xs = synth.hidden_states(shape, seed + 9, B)
+    want = ora.decode(xs)
+    check_close(to_host(gpu.decode(to_dev(shape, xs), B, 600)), want, "bf16", "GQA ragged step, max_ctx understated")
+    gpu.close()
+
+
 def test_split_stages_equal_whole_stage():
     """Running layers [0,k) then [k,L) as two stages equals one stage [0,L)."""
     shape, seed, lengths = MINI_BF16.with_(vocab=0), 5, [33, 8]
