@@ -1,27 +1,61 @@
-// bf16 MFMA GEMM for the prompt pass: C[M,N] = A[M,K] W[N,K]^T, fp32 accumulation.
+// bf16 MFMA GEMM for the prompt pass: C[M,N] = A[M,K] W[N,K]^T, fp32 accumulation, built on
+// v_mfma_f32_16x16x32_bf16.
 //
-// One 512-thread workgroup (8 wavefronts, 2 x 4) owns a 256 x 256 tile of C and walks K in
-// steps of 64.  Both operands are K-contiguous, so a lane's 16-byte global load is exactly
-// the 8-element K slice an MFMA operand wants.  Tiles go from global memory straight into
-// LDS (global_load_lds_dwordx4: no staging registers, no LDS store instructions) through a
-// ring of NS stages: two stages of 64 KB by default.  One such instruction fills 1 KB = 8
-// tile rows of 128 bytes; 16-byte chunks are XOR-swizzled by (row/2)&7 -- the lane that
-// fills physical chunk p of row r fetches logical chunk p ^ ((r/2)&7) -- so that the 16 rows
-// a quarter-wave reads for an MFMA operand fall into different banks (LDS has 64 banks
-// here).  v_mfma_f32_32x32x16_bf16: the activation tile is the A operand (rows m), the
-// weight tile the B operand (columns n); in the result a lane holds column n = lane%32 and
-// rows 8*(r/4) + 4*(lane/32) + r%4, r = 0..15.
+// Why this instruction: dense MFMA work on this chip is limited by power, not by issue slots.
+// A register-only loop of v_mfma_f32_32x32x16_bf16 with varied operands settles at about
+// 1.8 GHz (1.82 PFLOP/s), the same loop of v_mfma_f32_16x16x32_bf16 at 2.15 GHz
+// (2.2 PFLOP/s), both at 2.4 GHz with all-zero operands: per multiply-add the 16x16x32 form
+// moves half the fp32 accumulator bytes through the register file.  A first version of this
+// kernel on the 32x32x16 form ran its k-loop at 1.75 GHz, this one runs at 2.0 GHz.
 //
-// K-step width and ring depth are compile-time (LS_GEMM_BK 64 or 32, LS_GEMM_NS stages).
-// Measured inside the stage: rings of 3, 4 and 5 stages of 32-wide K steps all run 6% slower
-// than two stages of 64.  The depth of the ring does not matter; the rate at which one CU
-// pulls lines out of L2 does (its vector cache sits stalled on outstanding requests for 44%
-// of the kernel's cycles, L2 hit rate 79%), and 64-byte row pieces cost twice the requests
-// of whole 128-byte lines.
+// Tile and data path: one 512-thread workgroup (8 wavefronts, 2 x 4) owns a 256 x 256 tile of
+// C and walks K in steps of 64.  Both operands are K-contiguous, so a lane's 16-byte global
+// load is exactly the 8-element K slice an MFMA operand wants.  Tiles go from global memory
+// straight into LDS (global_load_lds_dwordx4: no staging registers, no LDS store
+// instructions) into a ring of two stages of 64 KB (LDS has no room for a third at this tile
+// size, and rings of narrower k-steps measured slower: 64-byte row pieces cost twice the
+// requests of whole 128-byte lines).  One such instruction fills 1 KB = 8 tile rows of 128
+// bytes; 16-byte chunks are XOR-swizzled by (row/2)&7 -- the lane that fills physical chunk p
+// of row r fetches logical chunk p ^ ((r/2)&7) -- so that the 16 rows a quarter-wave reads for
+// an MFMA operand fall into different banks (LDS has 64 banks here).
+//
+// A wavefront owns 128 rows x 64 columns of C = 8 x 4 MFMA tiles of 16 x 16.  The weight
+// fragment is the instruction's A operand and the activation fragment its B operand, so in
+// the result a lane holds row m = lane%16 of the tile and FOUR CONSECUTIVE columns
+// n = 4*(lane/16) .. +3: the epilogues store 8 or 16 bytes per lane.
+//
+// The k-loop is written out in issue order.  A k-step is two half-steps of 32 MFMAs (k = 32
+// each).  Within a half-step the activation fragments of row blocks 0..5 live in ONE set of
+// registers: the fragment of row block i is used by four consecutive MFMAs and reloaded for
+// the next half-step right after the last of them, 28 MFMAs before it is needed again; the
+// four weight fragments and the activation fragments of row blocks 6 and 7 are double
+// buffered.  The LDS reads are inline assembly and the waits for them are explicit
+// s_waitcnt lgkmcnt(n) with the exact number of younger reads that may still be in flight:
+// the compiler, which treats an LDS-direct load as a possible writer of anything in LDS, waits
+// for ALL outstanding LDS reads before every dependent MFMA once such a load is in the
+// function.  LDS reads return in order; the counts are derived next to the macro that issues
+// them.
+//
+// Stage hand-over: the barrier sits between the two half-steps of a k-step.  Before it a
+// wavefront has issued and completed every read of the stage being retired (the second
+// half-step's fragments were all requested during the first) and has seen its own fills of
+// the next stage land; after it the second half-step computes from registers, requests the
+// next stage's first fragments and issues the fills that refill the retired stage, one after
+// every fourth MFMA.
+//
+// What bounds it, from shader-clock stamps around the hand-over (development build): a k-step
+// takes about 2800 cycles at 2.0 GHz where its 256 MFMAs per SIMD need 2048.  On every SIMD
+// the older of the two wavefronts finishes its half of the work after about 1750 cycles, the
+// younger after about 2500; the barrier costs about 150.  Without any fills the same loop
+// takes about 2350 cycles at 2.3 GHz, and what the fills cost is power first (the clock), wall
+// time second: with fills whose lines all hit L2 the loop ran no faster, with a third fewer
+// LDS reads 2 % faster.  Fills that miss L2 did cost wall time until the prefetch below.
 //
 // Workgroup ids are remapped so that the 32 workgroups resident on one XCD (ids congruent
-// modulo 8 land on the same XCD) work on a 4 x 8 patch of neighbouring tiles and share
-// their operand tiles through that XCD's L2.
+// modulo 8 land on the same XCD) work on a 4 x 8 patch of neighbouring tiles and share their
+// operand panels through that XCD's L2, and so that the eight XCDs work on the eight patches
+// of one 16 x 16 block of tiles at the same time and find each other's panels in the
+// memory-side cache (+1.2 % over patches that are far apart).
 #include "kernels.hpp"
 #include "device_util.hpp"
 
@@ -29,72 +63,42 @@ namespace ls {
 
 namespace {
 
-#ifndef LS_GEMM_BK
-#define LS_GEMM_BK 64
-#endif
-#ifndef LS_GEMM_NS
-#define LS_GEMM_NS 2
-#endif
-#ifndef LS_GEMM_WAVES
-#define LS_GEMM_WAVES 8
-#endif
-constexpr int BM = 256, BN = 256, BK = LS_GEMM_BK;
-constexpr int NWAVE = LS_GEMM_WAVES;            // wavefronts per workgroup: 8 (2 x 4) or 4 (2 x 2)
-constexpr int WCOLS = NWAVE / 2;                // wavefronts side by side along N
-constexpr int TJ = BN / (WCOLS * 32);           // 32-column MFMA tiles per wavefront: 2 or 4
-constexpr int NS = LS_GEMM_NS;                  // ring of NS stages, NS-1 fills in flight
-constexpr int ROWB = BK * 2;                    // bytes per tile row
-constexpr int CH = ROWB / 16;                   // 16-byte chunks per row
-constexpr int RPI = 1024 / ROWB;                // rows per fill instruction
-constexpr int FROWS = BM / NWAVE;               // tile rows of each operand that one wavefront fills
-constexpr int FI = FROWS / RPI;                 // fill instructions per operand per wave
-constexpr int KK = BK / 16;                     // MFMA k-steps per stage
-constexpr int SH = (BK == 64) ? 1 : 2;          // swizzle: rows that share a bank group
-constexpr int TILE_BYTES = BM * ROWB;           // per operand tile
+constexpr int BM = 256, BN = 256, BK = 64;
+constexpr int NWAVE = 8;
+constexpr int ROWB = BK * 2;               // bytes per tile row
+constexpr int TILE_BYTES = BM * ROWB;      // 32 KB per operand tile
 constexpr int STAGE_BYTES = 2 * TILE_BYTES;
-constexpr int SMEM_BYTES = NS * STAGE_BYTES;
-constexpr int GROUP_M = 4;
-// s_waitcnt vmcnt(n), other counters untouched: all fills but those of the last NS-2 stages
-constexpr int VM_KEEP = 2 * FI * (NS - 2);
-constexpr int WAIT_KEEP = 0x0F70 | (VM_KEEP & 15) | ((VM_KEEP >> 4) << 14);
+constexpr int SMEM_BYTES = 2 * STAGE_BYTES;
+constexpr int FI = 4;                      // fill instructions per operand per wavefront and stage
+constexpr int PF_AHEAD = 1;                // k-steps between the L2 prefetch of a line and its fill
 
-__device__ __forceinline__ int swz(int row, int chunk) {
-  return row * ROWB + ((chunk ^ ((row >> SH) & (CH - 1))) << 4);
+__device__ __forceinline__ unsigned swz(int row, int chunk) {
+  return (unsigned)(row * ROWB + ((chunk ^ ((row >> 1) & 7)) << 4));
 }
+
 
 template <int EPI>
 __global__ void __launch_bounds__(NWAVE * 64, 1)
 k_gemm_mfma(const bf16* __restrict__ A, const bf16* __restrict__ W, int M, int N, int K,
-            void* __restrict__ outv, float* __restrict__ resid, int tiles_m, int tiles_n) {
+              void* __restrict__ outv, float* __restrict__ resid, int tiles_m, int tiles_n) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  typedef __attribute__((address_space(3))) void lds_void;
   constexpr bool GLU = (EPI == EPI_SWIGLU);
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave / WCOLS, wn = wave % WCOLS;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave >> 2, wn = wave & 3;
+  const int l16 = lane & 15, lq = lane >> 4;
 
-  // ---- workgroup id -> tile
+  // ---- workgroup id -> tile: the 32 workgroups resident on one XCD (ids congruent modulo 8)
+  // work on a 4 x 8 patch of neighbouring tiles and share operand panels through its L2
   const int nt = tiles_m * tiles_n;
-#ifndef LS_GEMM_MAP
-#define LS_GEMM_MAP 0
-#endif
-#if LS_GEMM_MAP == 0
-  const int per_xcd = (nt + 7) >> 3;
-  const int l = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-#else
-  // chunks of 32 consecutive tiles go round-robin over the 8 XCDs
+  // chunks of 32 consecutive tiles go round-robin over the 8 XCDs; two-level order: groups of
+  // 16 tile rows; inside a group, columns of 8 tiles; inside a column, patches of 4 rows, row
+  // index fastest.  32 consecutive tiles are a 4 x 8 patch, 256 consecutive tiles (what the
+  // eight XCDs work on at the same time) a 16 x 16 block of the output.
   const int slot = blockIdx.x >> 3;
   const int l = ((slot >> 5) << 8) + ((blockIdx.x & 7) << 5) + (slot & 31);
-#endif
   if (l >= nt) return;
-#if LS_GEMM_MAP < 2
-  const int in_group = GROUP_M * tiles_n;
-  const int first_m = (l / in_group) * GROUP_M;
-  const int gsz = min(tiles_m - first_m, GROUP_M);
-  const int tm = first_m + (l % in_group) % gsz;
-  const int tn = (l % in_group) / gsz;
-#else
-  // two-level order: groups of 16 tile rows; inside a group, columns of 8 tiles; inside a
-  // column, patches of 4 rows, row index fastest.  32 consecutive tiles are a 4 x 8 patch, 256
-  // consecutive tiles a 16 x 16 block of the output (ragged edges shrink the pieces).
   const int sg_tiles = 16 * tiles_n;
   const int g = min(l / sg_tiles, (tiles_m - 1) >> 4);
   const int R = min(16, tiles_m - 16 * g);
@@ -107,223 +111,283 @@ k_gemm_mfma(const bf16* __restrict__ A, const bf16* __restrict__ W, int M, int N
   const int lk = lj - pm * 4 * w;
   const int tm = 16 * g + 4 * pm + lk % rr;
   const int tn = 8 * c + lk / rr;
-#endif
+  const int q4 = lk % rr, q8 = lk / rr;     // position inside the patch
+  const bool pf_full = rr == 4 && w == 8;   // a whole 4 x 8 patch: its 32 workgroups run side by side on one XCD
   const int m0 = tm * BM;
   const int n0 = GLU ? tn * (BN / 2) : tn * BN;  // GLU: 128 output columns per tile
 
   // ---- global -> LDS: wave w fills tile rows 32w..32w+31 of both operands, 8 rows per
-  // instruction; lane l supplies row 32w + 8i + l/8, physical chunk l%8
-  const bf16* ap[FI];
-  const bf16* wp[FI];
+  // instruction; lane l supplies row 32w + 8i + l/8, physical chunk l%8.  Byte offsets from
+  // the operand's base (both operands are below 4 GB): the k-block's offset is added to the
+  // scalar base, so a fill costs no vector address arithmetic.
+  unsigned ao[FI], wo[FI];
 #pragma unroll
   for (int i = 0; i < FI; ++i) {
-    const int row = wave * FROWS + i * RPI + lane / CH;
-    const int c = (lane % CH) ^ ((row >> SH) & (CH - 1));
+    const int row = wave * 32 + i * 8 + (lane >> 3);
+    const int c = (lane & 7) ^ ((row >> 1) & 7);
     const int am = min(m0 + row, M - 1);
-    ap[i] = A + (size_t)am * K + c * 8;
+    ao[i] = (unsigned)(((size_t)am * K + c * 8) * 2);
     int wrow;
     if constexpr (GLU) {
-      // tile row -> weight row: 32-row blocks alternate gate / up, so that a wave's two
-      // column tiles are the gate and the up projection of the same 32 output columns
+      // tile row -> weight row: 32-row blocks alternate gate / up, so that a wave's 64 tile
+      // rows are the gate and the up projection of the same 32 output columns
       const int blk = row >> 5;
       const int f = min(n0 + (blk >> 1) * 32 + (row & 31), N - 1);
       wrow = (blk & 1) * N + f;
     } else {
       wrow = min(n0 + row, N - 1);
     }
-    wp[i] = W + (size_t)wrow * K + c * 8;
+    wo[i] = (unsigned)(((size_t)wrow * K + c * 8) * 2);
   }
-  f32x16 acc[4][TJ];
-#pragma unroll
-  for (int i = 0; i < 4; ++i)
-#pragma unroll
-    for (int j = 0; j < TJ; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+  const int fill_off = wave * 32 * ROWB;
+  // ---- L2 prefetch.  A weight panel is shared by the 4 workgroups of a patch column, an
+  // activation panel by the 8 of a patch row; whoever asks first waits for HBM or the
+  // memory-side cache, and with two LDS stages a fill has one k-step to land.  So every
+  // workgroup touches its share of the patch's lines PF_AHEAD k-steps before they are filled:
+  // 64 of the 256 weight rows and 32 of the 256 activation rows, i.e. 8 + 4 lines per wavefront
+  // and k-step, fetched by one 4-byte LDS-direct load (its lanes share those 12 lines; the
+  // words go to a scratch piece of LDS nobody reads).  It is the youngest vector memory
+  // operation of the wavefront at every hand-over, which therefore waits for all but one
+  // (vmcnt(1)): vector memory loads return in order.  Measured at the 13B shape: the waits for
+  // fills at the hand-over (300-700 cycles per k-step without it) disappear, +4.4 %.
+  const char* pf_ptr;
+  {
+    const int p = (lane & 15) < 12 ? (lane & 15) : (lane & 7);  // 12 distinct lines per wavefront
+    const int row_w = (pf_full ? 64 * q4 : 0) + 8 * wave + (p & 7);
+    const int row_a = (pf_full ? 32 * q8 : 0) + 4 * wave + (p & 3);
+    int wrow;
+    if constexpr (GLU) {
+      const int blk = row_w >> 5;
+      const int f = min(n0 + (blk >> 1) * 32 + (row_w & 31), N - 1);
+      wrow = (blk & 1) * N + f;
+    } else {
+      wrow = min(n0 + row_w, N - 1);
+    }
+    const int am = min(m0 + row_a, M - 1);
+    pf_ptr = (p < 8) ? (const char*)W + (size_t)wrow * K * 2 : (const char*)A + (size_t)am * K * 2;
+  }
+#define LS_PREFETCH(kb_)                                                                            \
+  __builtin_amdgcn_global_load_lds((const void*)(pf_ptr + (size_t)min((kb_), KT - 1) * (BK * 2)),   \
+                                   (lds_void*)(smem + SMEM_BYTES), 4, 0, 0);
+#define LS_FA(stage_, k0_, i_)                                                                        \
+  __builtin_amdgcn_global_load_lds((const void*)((const char*)A + (size_t)(k0_) * 2 + ao[i_]),        \
+      (lds_void*)(smem + (stage_) * STAGE_BYTES + fill_off + (i_) * 1024), 16, 0, 0);
+#define LS_FW(stage_, k0_, i_)                                                                        \
+  __builtin_amdgcn_global_load_lds((const void*)((const char*)W + (size_t)(k0_) * 2 + wo[i_]),        \
+      (lds_void*)(smem + (stage_) * STAGE_BYTES + TILE_BYTES + fill_off + (i_) * 1024), 16, 0, 0);
 
-  const int lr = lane & 31, lh = lane >> 5;
+  f32x4 acc[8][4];
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  // ---- LDS addresses of this lane's fragment reads in stage 0: fragment = 16 tile rows x 32 k,
+  // lane -> row lane%16, k-octet lane/16 (first half-step) or 4 + lane/16 (second); later row
+  // blocks are +2048 bytes (the swizzle term depends on row%16 only), stage 1 is +STAGE_BYTES
+  const unsigned lds0 = (unsigned)(size_t)(lds_void*)smem;
+  const unsigned xa0 = lds0 + swz(wm * 128 + l16, lq), xa1 = lds0 + swz(wm * 128 + l16, 4 + lq);
+  const unsigned wa0 = lds0 + TILE_BYTES + swz(wn * 64 + l16, lq);
+  const unsigned wa1 = lds0 + TILE_BYTES + swz(wn * 64 + l16, 4 + lq);
   const int KT = K / BK;
-  // LDS byte offsets of this lane's operand reads
-  int a_off[KK][4], b_off[KK][TJ];
-#pragma unroll
-  for (int kk = 0; kk < KK; ++kk) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) a_off[kk][i] = swz(wm * 128 + i * 32 + lr, kk * 2 + lh);
-#pragma unroll
-    for (int j = 0; j < TJ; ++j) b_off[kk][j] = TILE_BYTES + swz(wn * (TJ * 32) + j * 32 + lr, kk * 2 + lh);
-  }
-  typedef __attribute__((address_space(3))) void lds_void;
-  const int fill_off = (wave * FROWS) * ROWB;  // this wave's first row inside an operand tile
 
-#define LS_FILL_TILE(buf, k0)                                                                          \
-  _Pragma("unroll") for (int i = 0; i < FI; ++i) {                                                     \
-    __builtin_amdgcn_global_load_lds((const void*)(ap[i] + (k0)),                                      \
-        (lds_void*)(smem + (buf) * STAGE_BYTES + fill_off + i * 1024), 16, 0, 0);                      \
-    __builtin_amdgcn_global_load_lds((const void*)(wp[i] + (k0)),                                      \
-        (lds_void*)(smem + (buf) * STAGE_BYTES + TILE_BYTES + fill_off + i * 1024), 16, 0, 0);         \
-  }
-  // operand fragments are double buffered in registers: the LDS reads of k-step kk+1 are
-  // issued before the MFMAs of k-step kk, so the matrix pipe does not wait on LDS latency
-#define LS_READ_FRAGS(buf, kk, set)                                                                \
-  {                                                                                                \
-    _Pragma("unroll") for (int i = 0; i < 4; ++i)                                                  \
-      af[set][i] = *reinterpret_cast<const bf16x8*>(smem + (buf) * STAGE_BYTES + a_off[kk][i]); \
-    _Pragma("unroll") for (int j = 0; j < TJ; ++j)                                                 \
-      bfr[set][j] = *reinterpret_cast<const bf16x8*>(smem + (buf) * STAGE_BYTES + b_off[kk][j]); \
-  }
-#define LS_MFMA_STEP(set)                                                                          \
-  _Pragma("unroll") for (int i = 0; i < 4; ++i)                                                    \
-    _Pragma("unroll") for (int j = 0; j < TJ; ++j)                                                 \
-      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[set][i], bfr[set][j], acc[i][j], 0, 0, 0);
-  // within a k-step the six fragment reads of the next k-step are spread between the eight
-  // MFMAs (one read after each of the first six) instead of being issued as one burst
-#define LS_INTERLEAVE()                                                         \
-  _Pragma("unroll") for (int g_ = 0; g_ < 4 + TJ; ++g_) {                       \
-    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0); /* one MFMA */           \
-    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0); /* one LDS read */       \
-  }                                                                             \
-  __builtin_amdgcn_sched_group_barrier(0x008, 4 * TJ - (4 + TJ), 0);
-#define LS_COMPUTE_TILE(buf)                                    \
-  {                                                             \
-    bf16x8 af[2][4], bfr[2][TJ];                                \
-    LS_READ_FRAGS(buf, 0, 0)                                    \
-    __builtin_amdgcn_sched_barrier(0);                          \
-    _Pragma("unroll") for (int kk = 0; kk < KK; ++kk) {         \
-      if (kk + 1 < KK) LS_READ_FRAGS(buf, kk + 1, (kk + 1) & 1) \
-      LS_MFMA_STEP(kk & 1)                                      \
-      if (kk + 1 < KK) {                                        \
-        LS_INTERLEAVE()                                         \
-        __builtin_amdgcn_sched_barrier(0);                      \
-      }                                                         \
-    }                                                           \
-  }
-  // the barrier between k-steps: this wave's LDS reads are done (lgkmcnt) and the fills it
-  // issued for the next stage have landed (vmcnt; younger fills stay in flight)
-#define LS_STEP_BARRIER(imm)                 \
+  bf16x8 xf[6], xe[2][2], wf[2][4];
+#define LS_SB() __builtin_amdgcn_sched_barrier(0);
+#define LS_RD(dst_, addr_, off_) \
+  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst_) : "v"(addr_), "n"(off_));
+  // wait until at most n_ of this wavefront's LDS reads are outstanding (other counters untouched)
+#define LS_WAITL(n_) __builtin_amdgcn_s_waitcnt(0xC07F | ((n_) << 8));
+  // activation fragment of row block i_ in half-step parity ws_: blocks 0..5 live in one set of
+  // registers, blocks 6 and 7 in two (see below)
+#define LS_X(ws_, i_) ((i_) < 6 ? xf[(i_) < 6 ? (i_) : 0] : xe[ws_][(i_) < 6 ? 0 : (i_) - 6])
+#define LS_MF(ws_, i_, j_) \
+  acc[i_][j_] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[ws_][j_], LS_X(ws_, i_), acc[i_][j_], 0, 0, 0);
+#define LS_NONE
+  // One row block of a half-step: four MFMAs; after the second the reads WR_ (the next
+  // half-step's weight fragment i_, row blocks 0..3 only), after the third an optional fill
+  // (F_), after the fourth the read XR_ (the row block's own activation fragment for the next
+  // half-step, row blocks 0..5).
+#define LS_BLOCK(ws_, i_, WR_, F_, XR_)                             \
+  LS_MF(ws_, i_, 0) LS_SB()                                         \
+  LS_MF(ws_, i_, 1) LS_SB()                                         \
+  WR_ LS_SB()                                                       \
+  LS_MF(ws_, i_, 2) LS_SB()                                         \
+  F_ LS_SB()                                                        \
+  LS_MF(ws_, i_, 3) LS_SB()                                         \
+  XR_ LS_SB()
+  // A half-step.  The fragments of row blocks 6 and 7 are double buffered and requested early
+  // (with the weight fragments of row blocks 2 and 3), so that the last read before the
+  // hand-over barrier is eight MFMAs old when the barrier waits for it.  Reads are issued in
+  // the order W0' X0' W1' X1' W2' X6' X2' W3' X7' X3' X4' X5' (primes: for the next half-step).
+  // Row block 0 needs X0 and all of W0..W3, i.e. the first eight reads of the previous
+  // half-step: four younger ones may be outstanding.  Row blocks 1 and 2 are covered by that
+  // wait.  Row block 3 needs X3, the tenth: two younger ones of the previous half-step plus the
+  // seven issued so far in this one.  Row block 4 needs the eleventh: one younger plus ten of
+  // this half-step; row block 5 the twelfth: none plus eleven.  Row blocks 6 and 7 need the
+  // sixth and the ninth, which the waits of row blocks 0 and 3 have covered.
+#define LS_HALF(ws_, xaddr_, waddr_, F0, F1, F2, F3, F4, F5, F6, F7)                                   \
+  LS_WAITL(4) LS_SB()                                                                                  \
+  LS_BLOCK(ws_, 0, LS_RD(wf[(ws_) ^ 1][0], waddr_, 0 * 2048), F0, LS_RD(xf[0], xaddr_, 0 * 2048))      \
+  LS_BLOCK(ws_, 1, LS_RD(wf[(ws_) ^ 1][1], waddr_, 1 * 2048), F1, LS_RD(xf[1], xaddr_, 1 * 2048))      \
+  LS_BLOCK(ws_, 2, LS_RD(wf[(ws_) ^ 1][2], waddr_, 2 * 2048) LS_RD(xe[(ws_) ^ 1][0], xaddr_, 6 * 2048), \
+           F2, LS_RD(xf[2], xaddr_, 2 * 2048))                                                         \
+  LS_WAITL(9) LS_SB()                                                                                  \
+  LS_BLOCK(ws_, 3, LS_RD(wf[(ws_) ^ 1][3], waddr_, 3 * 2048) LS_RD(xe[(ws_) ^ 1][1], xaddr_, 7 * 2048), \
+           F3, LS_RD(xf[3], xaddr_, 3 * 2048))                                                         \
+  LS_WAITL(11) LS_SB()                                                                                 \
+  LS_BLOCK(ws_, 4, LS_NONE, F4, LS_RD(xf[4], xaddr_, 4 * 2048))                                        \
+  LS_WAITL(11) LS_SB()                                                                                 \
+  LS_BLOCK(ws_, 5, LS_NONE, F5, LS_RD(xf[5], xaddr_, 5 * 2048))                                        \
+  LS_BLOCK(ws_, 6, LS_NONE, F6, LS_NONE)                                                               \
+  LS_BLOCK(ws_, 7, LS_NONE, F7, LS_NONE)
+  // own LDS reads done, own fills landed, then everyone
+#define LS_HANDOVER(imm_)                    \
   asm volatile("" ::: "memory");             \
-  __builtin_amdgcn_s_waitcnt(imm);           \
-  __builtin_amdgcn_s_waitcnt(0xC07F);        \
+  __builtin_amdgcn_s_waitcnt(imm_);          \
   __builtin_amdgcn_sched_barrier(0);         \
   __builtin_amdgcn_s_barrier();              \
   __builtin_amdgcn_sched_barrier(0);         \
   asm volatile("" ::: "memory");
 
-#ifndef LS_GEMM_ROT
-#define LS_GEMM_ROT 1
-#endif
-#if LS_GEMM_ROT
-  // The loop is rotated by one MFMA group: the barrier that hands over the next stage sits
-  // BEFORE the last group of a k-step, so that group's MFMAs run while the first operand
-  // fragments of the next stage are on their way from LDS, and neither wavefront of a SIMD
-  // starts a k-step by waiting for LDS.  Right after the barrier the stage just read out is
-  // refilled, which leaves its fills a whole k-step to land, as before.
-  static_assert(NS == 2 && KK % 2 == 0, "the rotated loop alternates two stages and two fragment sets");
-  {
-    bf16x8 af[2][4], bfr[2][TJ];
-    LS_FILL_TILE(0, 0)
-    LS_STEP_BARRIER(0x0F70)
-    if (KT > 1) LS_FILL_TILE(1, BK)
-    LS_READ_FRAGS(0, 0, 0)
-    __builtin_amdgcn_sched_barrier(0);
-    for (int kt = 0; kt + 1 < KT; ++kt) {
-      const int buf = kt & 1;
+  // ---- prologue: stage 0 <- k-block 0, hand over, stage 1 <- k-block 1, first fragments
 #pragma unroll
-      for (int kk = 0; kk + 1 < KK; ++kk) {
-        LS_READ_FRAGS(buf, kk + 1, (kk + 1) & 1)
-        LS_MFMA_STEP(kk & 1)
-        LS_INTERLEAVE()
-        __builtin_amdgcn_sched_barrier(0);
-      }
-      // stage kt+1 has landed for every wavefront, and every wavefront has read all of stage kt
-      LS_STEP_BARRIER(0x0F70)
-      if (kt + 2 < KT) LS_FILL_TILE(buf, (kt + 2) * BK)
-      LS_READ_FRAGS(buf ^ 1, 0, 0)
-      LS_MFMA_STEP(1)
-      LS_INTERLEAVE()
-      __builtin_amdgcn_sched_barrier(0);
-    }
-    {  // the last k-step has nothing to hand over
-      const int buf = (KT - 1) & 1;
+  for (int i = 0; i < FI; ++i) {
+    LS_FA(0, 0, i)
+    LS_FW(0, 0, i)
+  }
+  LS_HANDOVER(0x0070)
+  if (KT > 1) {
 #pragma unroll
-      for (int kk = 0; kk + 1 < KK; ++kk) {
-        LS_READ_FRAGS(buf, kk + 1, (kk + 1) & 1)
-        LS_MFMA_STEP(kk & 1)
-        LS_INTERLEAVE()
-        __builtin_amdgcn_sched_barrier(0);
-      }
-      LS_MFMA_STEP(1)
+    for (int i = 0; i < FI; ++i) {
+      LS_FA(1, BK, i)
+      LS_FW(1, BK, i)
     }
   }
-#else
-#pragma unroll
-  for (int s = 0; s < NS - 1; ++s)
-    if (s < KT) LS_FILL_TILE(s, s * BK)
-  if (KT >= NS - 1) { LS_STEP_BARRIER(WAIT_KEEP) } else { LS_STEP_BARRIER(0x0F70) }
-  for (int kt = 0; kt < KT; ++kt) {
-    const int buf = kt % NS;
-    // stage (kt-1) % NS was last read in step kt-1, which every wave has left (barrier)
-    const bool more = kt + NS - 1 < KT;
-    if (more) LS_FILL_TILE((kt + NS - 1) % NS, (kt + NS - 1) * BK)
-    LS_COMPUTE_TILE(buf)
-    if (more) { LS_STEP_BARRIER(WAIT_KEEP) } else { LS_STEP_BARRIER(0x0F70) }
-  }
-#endif
-#undef LS_FILL_TILE
-#undef LS_COMPUTE_TILE
-#undef LS_INTERLEAVE
-#undef LS_READ_FRAGS
-#undef LS_MFMA_STEP
-#undef LS_STEP_BARRIER
+  LS_PREFETCH(1 + PF_AHEAD)
+  LS_SB()
+  LS_RD(wf[0][0], wa0, 0 * 2048) LS_RD(xf[0], xa0, 0 * 2048)
+  LS_RD(wf[0][1], wa0, 1 * 2048) LS_RD(xf[1], xa0, 1 * 2048)
+  LS_RD(wf[0][2], wa0, 2 * 2048) LS_RD(xe[0][0], xa0, 6 * 2048) LS_RD(xf[2], xa0, 2 * 2048)
+  LS_RD(wf[0][3], wa0, 3 * 2048) LS_RD(xe[0][1], xa0, 7 * 2048) LS_RD(xf[3], xa0, 3 * 2048)
+  LS_RD(xf[4], xa0, 4 * 2048) LS_RD(xf[5], xa0, 5 * 2048)
+  LS_SB()
 
-  // ---- epilogue
-  if constexpr (EPI == EPI_RESID) {
-    // fp32 read-modify-write of the residual rows.  A store to `resid` may alias a later load
-    // as far as the compiler can tell, so "resid[o] += acc" element by element would wait one
-    // memory round trip per element; here the 16 old values of the NEXT 32 x 32 tile are
-    // requested before the current tile's sums are stored, so every lane always has 16 loads in
-    // flight behind its stores.
-    float old[2][16];
-    const int ncol = n0 + wn * (TJ * 32) + lr;
-#define LS_RESID_LOAD(t, set)                                                                       \
-  _Pragma("unroll") for (int r = 0; r < 16; ++r) {                                                  \
-    const int m_ = m0 + wm * 128 + ((t) / TJ) * 32 + 8 * (r >> 2) + 4 * lh + (r & 3);               \
-    const int n_ = ncol + ((t) % TJ) * 32;                                                          \
-    old[set][r] = (m_ < M && n_ < N) ? resid[(size_t)m_ * N + n_] : 0.f;                            \
-  }
-    LS_RESID_LOAD(0, 0)
-#pragma unroll
-    for (int t = 0; t < 4 * TJ; ++t) {
-      if (t + 1 < 4 * TJ) LS_RESID_LOAD(t + 1, (t + 1) & 1)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int m = m0 + wm * 128 + (t / TJ) * 32 + 8 * (r >> 2) + 4 * lh + (r & 3);
-        const int n = ncol + (t % TJ) * 32;
-        if (m < M && n < N) resid[(size_t)m * N + n] = old[t & 1][r] + acc[t / TJ][t % TJ][r];
-      }
+  for (int kt = 0; kt < KT; ++kt) {
+    const int buf = kt & 1;
+    const unsigned sx = (unsigned)buf * STAGE_BYTES, so = (unsigned)(buf ^ 1) * STAGE_BYTES;
+    // first half-step: computes k-octets 0..3 of stage buf, requests octets 4..7 of the same stage
+    {
+      const unsigned xa = xa1 + sx, wa = wa1 + sx;
+      LS_SB()
+      LS_HALF(0, xa, wa, LS_NONE, LS_NONE, LS_NONE, LS_NONE, LS_NONE, LS_NONE, LS_NONE, LS_NONE)
     }
-#undef LS_RESID_LOAD
+    LS_HANDOVER(0x0071)  // vmcnt(1): all fills, not the youngest prefetch
+    // second half-step: computes octets 4..7, requests octets 0..3 of the other stage (the last
+    // k-step requests fragments nobody uses; they are drained below) and refills stage buf
+    {
+      const unsigned xa = xa0 + so, wa = wa0 + so;
+      // the last two k-steps have nothing left to fetch: they fill the retired stage once more
+      // with the last k-block (lines that are in L2 anyway) instead of branching around every fill
+      const int k2 = min(kt + 2, KT - 1) * BK;
+      LS_SB()
+      LS_HALF(1, xa, wa, LS_FA(buf, k2, 0), LS_FW(buf, k2, 0), LS_FA(buf, k2, 1), LS_FW(buf, k2, 1), LS_FA(buf, k2, 2),
+              LS_FW(buf, k2, 2), LS_FA(buf, k2, 3), LS_FW(buf, k2, 3) LS_PREFETCH(kt + 2 + PF_AHEAD))
+    }
+  }
+  // the reads requested by the last half-step land in registers the epilogue may reuse, and no
+  // LDS-direct load may still be on its way when the workgroup gives up its LDS
+  LS_SB()
+  __builtin_amdgcn_s_waitcnt(0x0070);
+  LS_SB()
+#undef LS_FA
+#undef LS_FW
+#undef LS_SB
+#undef LS_RD
+#undef LS_WAITL
+#undef LS_MF
+#undef LS_X
+#undef LS_NONE
+#undef LS_BLOCK
+#undef LS_HALF
+#undef LS_HANDOVER
+#undef LS_PREFETCH
+
+  // ---- epilogue: acc[i][j][r] is C[m0 + 128 wm + 16 i + lane%16][n0 + 64 wn + 16 j + 4 (lane/16) + r]
+  const bool vec = (N & 3) == 0;
+  if constexpr (EPI == EPI_RESID) {
+    // fp32 read-modify-write of the residual rows, 16 bytes per lane; the eight old values of
+    // two row blocks are requested before the first sum is stored
+#pragma unroll
+    for (int i2 = 0; i2 < 8; i2 += 2) {
+      f32x4 old[2][4];
+#pragma unroll
+      for (int ii = 0; ii < 2; ++ii)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const int m = m0 + wm * 128 + (i2 + ii) * 16 + l16;
+          const int n = n0 + wn * 64 + j * 16 + 4 * lq;
+          const float* p = resid + (size_t)m * N + n;
+          if (m < M && vec && n + 3 < N) old[ii][j] = *reinterpret_cast<const f32x4*>(p);
+          else
+#pragma unroll
+            for (int r = 0; r < 4; ++r) old[ii][j][r] = (m < M && n + r < N) ? p[r] : 0.f;
+        }
+#pragma unroll
+      for (int ii = 0; ii < 2; ++ii)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const int m = m0 + wm * 128 + (i2 + ii) * 16 + l16;
+          const int n = n0 + wn * 64 + j * 16 + 4 * lq;
+          float* p = resid + (size_t)m * N + n;
+          const f32x4 v = old[ii][j] + acc[i2 + ii][j];
+          if (m < M && vec && n + 3 < N) *reinterpret_cast<f32x4*>(p) = v;
+          else
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+              if (m < M && n + r < N) p[r] = v[r];
+        }
+    }
     return;
   }
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
+  for (int i = 0; i < 8; ++i) {
+    const int m = m0 + wm * 128 + i * 16 + l16;
+    if (m >= M) continue;
+    if constexpr (GLU) {
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      const int m = m0 + wm * 128 + i * 32 + 8 * (r >> 2) + 4 * lh + (r & 3);
-      if (m >= M) continue;
-      if constexpr (GLU) {
+      for (int j = 0; j < 2; ++j) {
+        const int n = n0 + wn * 32 + j * 16 + 4 * lq;
+        bf16x4 v;
 #pragma unroll
-        for (int jj = 0; jj < TJ / 2; ++jj) {
-          const int n = n0 + wn * (TJ * 16) + jj * 32 + lr;
-          if (n < N) ((bf16*)outv)[(size_t)m * N + n] = (bf16)(silu_f(acc[i][2 * jj][r]) * acc[i][2 * jj + 1][r]);
-        }
-      } else {
+        for (int r = 0; r < 4; ++r) v[r] = (bf16)(silu_f(acc[i][j][r]) * acc[i][j + 2][r]);
+        bf16* p = (bf16*)outv + (size_t)m * N + n;
+        if (vec && n + 3 < N) *reinterpret_cast<bf16x4*>(p) = v;
+        else
 #pragma unroll
-        for (int j = 0; j < TJ; ++j) {
-          const int n = n0 + wn * (TJ * 32) + j * 32 + lr;
-          if (n >= N) continue;
-          const size_t o = (size_t)m * N + n;
-          if constexpr (EPI == EPI_STORE) ((bf16*)outv)[o] = (bf16)acc[i][j][r];
-          else ((float*)outv)[o] = acc[i][j][r];
+          for (int r = 0; r < 4; ++r)
+            if (n + r < N) p[r] = v[r];
+      }
+    } else {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int n = n0 + wn * 64 + j * 16 + 4 * lq;
+        if constexpr (EPI == EPI_STORE) {
+          bf16x4 v;
+#pragma unroll
+          for (int r = 0; r < 4; ++r) v[r] = (bf16)acc[i][j][r];
+          bf16* p = (bf16*)outv + (size_t)m * N + n;
+          if (vec && n + 3 < N) *reinterpret_cast<bf16x4*>(p) = v;
+          else
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+              if (n + r < N) p[r] = v[r];
+        } else {
+          float* p = (float*)outv + (size_t)m * N + n;
+          if (vec && n + 3 < N) *reinterpret_cast<f32x4*>(p) = acc[i][j];
+          else
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+              if (n + r < N) p[r] = acc[i][j][r];
         }
       }
     }
@@ -333,18 +397,15 @@ k_gemm_mfma(const bf16* __restrict__ A, const bf16* __restrict__ W, int M, int N
 template <int EPI>
 void launch_t(const void* A, const void* W, int M, int N, int K, void* out, float* resid, hipStream_t st) {
   static std::atomic<uint64_t> lds_allowed{0};
-  allow_dynamic_lds((const void*)k_gemm_mfma<EPI>, SMEM_BYTES, lds_allowed);
+  constexpr int LDS_BYTES = SMEM_BYTES + 256;  // + the scratch words of the L2 prefetch
+  allow_dynamic_lds((const void*)k_gemm_mfma<EPI>, LDS_BYTES, lds_allowed);
   const int tiles_m = (M + BM - 1) / BM;
   const int ncols = (EPI == EPI_SWIGLU) ? BN / 2 : BN;
   const int tiles_n = (N + ncols - 1) / ncols;
   const int nt = tiles_m * tiles_n;
-#if LS_GEMM_MAP == 0
-  const int grid = ((nt + 7) / 8) * 8;
-#else
   const int grid = ((nt + 255) / 256) * 256;
-#endif
-  launch_kernel(k_gemm_mfma<EPI>, dim3(grid), dim3(NWAVE * 64), SMEM_BYTES, st, (const bf16*)A, (const bf16*)W, M, N, K, out,
-                resid, tiles_m, tiles_n);
+  launch_kernel(k_gemm_mfma<EPI>, dim3(grid), dim3(NWAVE * 64), LDS_BYTES, st, (const bf16*)A, (const bf16*)W, M, N,
+                K, out, resid, tiles_m, tiles_n);
 }
 
 }  // namespace
@@ -352,7 +413,7 @@ void launch_t(const void* A, const void* W, int M, int N, int K, void* out, floa
 bool gemm_mfma_supported(int M, int N, int K) { return M >= 1 && N >= 1 && K >= BK && K % BK == 0; }
 
 void launch_gemm_mfma(Epilogue epi, const void* A, const void* W, int M, int N, int K, void* out, float* resid,
-                      hipStream_t st) {
+                        hipStream_t st) {
   switch (epi) {
     case EPI_STORE: launch_t<EPI_STORE>(A, W, M, N, K, out, resid, st); break;
     case EPI_RESID: launch_t<EPI_RESID>(A, W, M, N, K, out, resid, st); break;
@@ -362,3 +423,4 @@ void launch_gemm_mfma(Epilogue epi, const void* A, const void* W, int M, int N, 
 }
 
 }  // namespace ls
+
