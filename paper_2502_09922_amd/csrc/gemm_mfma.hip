@@ -77,6 +77,29 @@ __device__ __forceinline__ unsigned swz(int row, int chunk) {
 }
 
 
+// Tile number l in the two-level order -> tile coordinates, position inside its 4 x 8 patch
+// (q4 of rr rows, q8 of w columns; ragged edges shrink the patch).
+struct TileAt { int tm, tn, q4, q8; bool full; };
+__device__ __forceinline__ TileAt tile_at(int l, int tiles_m, int tiles_n) {
+  const int sg_tiles = 16 * tiles_n;
+  const int g = min(l / sg_tiles, (tiles_m - 1) >> 4);
+  const int R = min(16, tiles_m - 16 * g);
+  const int li = l - g * sg_tiles;
+  const int c = min(li / (R * 8), (tiles_n - 1) >> 3);
+  const int w = min(8, tiles_n - 8 * c);
+  const int lj = li - c * R * 8;
+  const int pm = min(lj / (4 * w), (R - 1) >> 2);
+  const int rr = min(4, R - 4 * pm);
+  const int lk = lj - pm * 4 * w;
+  TileAt t;
+  t.tm = 16 * g + 4 * pm + lk % rr;
+  t.tn = 8 * c + lk / rr;
+  t.q4 = lk % rr;
+  t.q8 = lk / rr;
+  t.full = rr == 4 && w == 8;  // a whole patch: its 32 workgroups run side by side on one XCD
+  return t;
+}
+
 template <int EPI>
 __global__ void __launch_bounds__(NWAVE * 64, 1)
 k_gemm_mfma(const bf16* __restrict__ A, const bf16* __restrict__ W, int M, int N, int K,
@@ -99,20 +122,8 @@ k_gemm_mfma(const bf16* __restrict__ A, const bf16* __restrict__ W, int M, int N
   const int slot = blockIdx.x >> 3;
   const int l = ((slot >> 5) << 8) + ((blockIdx.x & 7) << 5) + (slot & 31);
   if (l >= nt) return;
-  const int sg_tiles = 16 * tiles_n;
-  const int g = min(l / sg_tiles, (tiles_m - 1) >> 4);
-  const int R = min(16, tiles_m - 16 * g);
-  const int li = l - g * sg_tiles;
-  const int c = min(li / (R * 8), (tiles_n - 1) >> 3);
-  const int w = min(8, tiles_n - 8 * c);
-  const int lj = li - c * R * 8;
-  const int pm = min(lj / (4 * w), (R - 1) >> 2);
-  const int rr = min(4, R - 4 * pm);
-  const int lk = lj - pm * 4 * w;
-  const int tm = 16 * g + 4 * pm + lk % rr;
-  const int tn = 8 * c + lk / rr;
-  const int q4 = lk % rr, q8 = lk / rr;     // position inside the patch
-  const bool pf_full = rr == 4 && w == 8;   // a whole 4 x 8 patch: its 32 workgroups run side by side on one XCD
+  const TileAt ta = tile_at(l, tiles_m, tiles_n);
+  const int tm = ta.tm, tn = ta.tn;
   const int m0 = tm * BM;
   const int n0 = GLU ? tn * (BN / 2) : tn * BN;  // GLU: 128 output columns per tile
 
@@ -140,6 +151,26 @@ k_gemm_mfma(const bf16* __restrict__ A, const bf16* __restrict__ W, int M, int N
     wo[i] = (unsigned)(((size_t)wrow * K + c * 8) * 2);
   }
   const int fill_off = wave * 32 * ROWB;
+#define LS_FA(stage_, k0_, i_)                                                                        \
+  __builtin_amdgcn_global_load_lds((const void*)((const char*)A + (size_t)(k0_) * 2 + ao[i_]),        \
+      (lds_void*)(smem + (stage_) * STAGE_BYTES + fill_off + (i_) * 1024), 16, 0, 0);
+#define LS_FW(stage_, k0_, i_)                                                                        \
+  __builtin_amdgcn_global_load_lds((const void*)((const char*)W + (size_t)(k0_) * 2 + wo[i_]),        \
+      (lds_void*)(smem + (stage_) * STAGE_BYTES + TILE_BYTES + fill_off + (i_) * 1024), 16, 0, 0);
+  // both stages are free when a workgroup starts: stage 0 <- k-block 0 and stage 1 <- k-block 1
+  // at once (K >= 2 k-blocks); everything up to the first hand-over is set up while these
+  // first fills, which nothing else overlaps, are on their way
+#pragma unroll
+  for (int i = 0; i < FI; ++i) {
+    LS_FA(0, 0, i)
+    LS_FW(0, 0, i)
+  }
+#pragma unroll
+  for (int i = 0; i < FI; ++i) {
+    LS_FA(1, BK, i)
+    LS_FW(1, BK, i)
+  }
+
   // ---- L2 prefetch.  A weight panel is shared by the 4 workgroups of a patch column, an
   // activation panel by the 8 of a patch row; whoever asks first waits for HBM or the
   // memory-side cache, and with two LDS stages a fill has one k-step to land.  So every
@@ -150,32 +181,32 @@ k_gemm_mfma(const bf16* __restrict__ A, const bf16* __restrict__ W, int M, int N
   // operation of the wavefront at every hand-over, which therefore waits for all but one
   // (vmcnt(1)): vector memory loads return in order.  Measured at the 13B shape: the waits for
   // fills at the hand-over (300-700 cycles per k-step without it) disappear, +4.4 %.
-  const char* pf_ptr;
-  {
+  // The last k-steps of a tile prefetch the first k-blocks of tile l + 256 instead: the tile
+  // that the same XCD starts next in this slot, whichever of its CUs gets it, so that a new
+  // workgroup's first fills, which nothing overlaps, find their lines in L2.
+  auto pf_base = [&](const TileAt& t) -> const char* {
     const int p = (lane & 15) < 12 ? (lane & 15) : (lane & 7);  // 12 distinct lines per wavefront
-    const int row_w = (pf_full ? 64 * q4 : 0) + 8 * wave + (p & 7);
-    const int row_a = (pf_full ? 32 * q8 : 0) + 4 * wave + (p & 3);
+    const int row_w = (t.full ? 64 * t.q4 : 0) + 8 * wave + (p & 7);
+    const int row_a = (t.full ? 32 * t.q8 : 0) + 4 * wave + (p & 3);
+    const int tn0 = GLU ? t.tn * (BN / 2) : t.tn * BN;
     int wrow;
     if constexpr (GLU) {
       const int blk = row_w >> 5;
-      const int f = min(n0 + (blk >> 1) * 32 + (row_w & 31), N - 1);
+      const int f = min(tn0 + (blk >> 1) * 32 + (row_w & 31), N - 1);
       wrow = (blk & 1) * N + f;
     } else {
-      wrow = min(n0 + row_w, N - 1);
+      wrow = min(tn0 + row_w, N - 1);
     }
-    const int am = min(m0 + row_a, M - 1);
-    pf_ptr = (p < 8) ? (const char*)W + (size_t)wrow * K * 2 : (const char*)A + (size_t)am * K * 2;
-  }
+    const int am = min(t.tm * BM + row_a, M - 1);
+    return (p < 8) ? (const char*)W + (size_t)wrow * K * 2 : (const char*)A + (size_t)am * K * 2;
+  };
+  const char* pf_ptr = pf_base(ta);
+  const char* pf_next = l + 256 < nt ? pf_base(tile_at(l + 256, tiles_m, tiles_n)) : pf_ptr;
 #define LS_PREFETCH(kb_)                                                                            \
-  __builtin_amdgcn_global_load_lds((const void*)(pf_ptr + (size_t)min((kb_), KT - 1) * (BK * 2)),   \
-                                   (lds_void*)(smem + SMEM_BYTES), 4, 0, 0);
-#define LS_FA(stage_, k0_, i_)                                                                        \
-  __builtin_amdgcn_global_load_lds((const void*)((const char*)A + (size_t)(k0_) * 2 + ao[i_]),        \
-      (lds_void*)(smem + (stage_) * STAGE_BYTES + fill_off + (i_) * 1024), 16, 0, 0);
-#define LS_FW(stage_, k0_, i_)                                                                        \
-  __builtin_amdgcn_global_load_lds((const void*)((const char*)W + (size_t)(k0_) * 2 + wo[i_]),        \
-      (lds_void*)(smem + (stage_) * STAGE_BYTES + TILE_BYTES + fill_off + (i_) * 1024), 16, 0, 0);
-
+  __builtin_amdgcn_global_load_lds(                                                                 \
+      (const void*)((kb_) < KT ? pf_ptr + (size_t)(kb_) * (BK * 2)                                  \
+                               : pf_next + (size_t)min((kb_) - KT, KT - 1) * (BK * 2)),             \
+      (lds_void*)(smem + SMEM_BYTES), 4, 0, 0);
   f32x4 acc[8][4];
 #pragma unroll
   for (int i = 0; i < 8; ++i)
@@ -249,21 +280,10 @@ k_gemm_mfma(const bf16* __restrict__ A, const bf16* __restrict__ W, int M, int N
   __builtin_amdgcn_sched_barrier(0);         \
   asm volatile("" ::: "memory");
 
-  // ---- prologue: stage 0 <- k-block 0, hand over, stage 1 <- k-block 1, first fragments
-#pragma unroll
-  for (int i = 0; i < FI; ++i) {
-    LS_FA(0, 0, i)
-    LS_FW(0, 0, i)
-  }
-  LS_HANDOVER(0x0070)
-  if (KT > 1) {
-#pragma unroll
-    for (int i = 0; i < FI; ++i) {
-      LS_FA(1, BK, i)
-      LS_FW(1, BK, i)
-    }
-  }
+  // ---- prologue: prefetch, hand over stage 0 (the eight fills of stage 1 and the prefetch may
+  // still be in flight: vmcnt(9)), first fragments
   LS_PREFETCH(1 + PF_AHEAD)
+  LS_HANDOVER(0x0079)
   LS_SB()
   LS_RD(wf[0][0], wa0, 0 * 2048) LS_RD(xf[0], xa0, 0 * 2048)
   LS_RD(wf[0][1], wa0, 1 * 2048) LS_RD(xf[1], xa0, 1 * 2048)
@@ -410,7 +430,7 @@ void launch_t(const void* A, const void* W, int M, int N, int K, void* out, floa
 
 }  // namespace
 
-bool gemm_mfma_supported(int M, int N, int K) { return M >= 1 && N >= 1 && K >= BK && K % BK == 0; }
+bool gemm_mfma_supported(int M, int N, int K) { return M >= 1 && N >= 1 && K >= 2 * BK && K % BK == 0; }
 
 void launch_gemm_mfma(Epilogue epi, const void* A, const void* W, int M, int N, int K, void* out, float* resid,
                         hipStream_t st) {
