@@ -5,17 +5,19 @@
 // are small matrix products and run on the matrix cores; the vector ALUs only do the softmax.
 // The kernel stays bound by streaming the cache out of HBM once per step.
 //
-//   * One workgroup per (sequence, kv head, chunk of 2048 keys); its NW wavefronts split the
+//   * One workgroup per (sequence, kv head, chunk of the context); its NW wavefronts split the
 //     chunk's 32-key tiles into contiguous runs (split-KV inside the workgroup, merged in wave
-//     order).  A sequence of up to 2048 keys is one workgroup, which writes the output row; a
-//     longer one is several workgroups, each of which leaves its running maximum, its sum and
-//     its un-normalised output in a scratch buffer, and a small second kernel adds them up in
-//     chunk order (a fixed order: the result does not depend on timing).  Measured at the 70B
-//     shape (64 ragged contexts of 128..2300 keys, 8 kv heads): chunks of 512 keys make the
-//     kernel 24 % slower, 1024 keys 11 %, 2048 keys change nothing -- a workgroup's start
-//     (query rotation, first tile) and end (merge through LDS) cost several microseconds, more
-//     than the ragged batch loses by waiting for its longest sequence; the chunks are there for
-//     contexts of many thousands of keys, where one workgroup per sequence would leave the chip idle.
+//     order).  A sequence that is one chunk is one workgroup, which writes the output row; a
+//     sequence of several chunks is several workgroups, each of which leaves its running
+//     maximum, its sum and its un-normalised output in a scratch buffer, and a small second
+//     kernel adds them up in chunk order (a fixed order: the result does not depend on timing).
+//     Measured at the 70B shape (64 ragged contexts of 128..2300 keys, 8 kv heads = 512
+//     workgroups): chunks of 512 keys make the kernel 24 % slower, 1024 keys 11 %, and two
+//     chunks per sequence with a merge kernel 12 us per layer slower than one -- a workgroup's
+//     start (query rotation, first tile) and end (merge through LDS, partial result) cost
+//     several microseconds, more than the ragged batch loses by waiting for its longest
+//     sequence.  So contexts are cut only where sequences x kv heads alone would leave the
+//     chip idle, or beyond 8192 keys (see the constants below).
 //   * A tile (32 keys x 256 bytes of K, the same of V) is fetched with sixteen 16-byte-per-lane
 //     non-temporal loads, a quarter-wave per cache row (whole rows, 1 KB per instruction), and
 //     goes through a wave-private LDS area (written lane-linear; the 16-byte chunks of a row
@@ -34,6 +36,8 @@
 //     with the value, and patched into the LDS tile that covers position `pos`, so it takes
 //     the same path as every cached key.  Cache rows past `pos` are never used: keys are
 //     masked before the exponential and their values are zeroed on the way into LDS.
+#include <algorithm>
+
 #include "kernels.hpp"
 #include "device_util.hpp"
 
@@ -44,10 +48,14 @@ namespace {
 constexpr int HD = 128;
 constexpr int TK = 32;                   // keys per tile
 constexpr int TILE_BYTES = TK * HD * 2;  // 8 KB of K, 8 KB of V
-#ifndef LS_GQA_TPC
-#define LS_GQA_TPC 64
-#endif
-constexpr int TPC = LS_GQA_TPC;          // tiles per chunk: 2048 keys (one chunk per sequence without scratch)
+// Chunking of long contexts.  One workgroup per (sequence, kv head) is the cheapest form: a
+// chunk's start (tables, query rotation, first tile) and end (partial result, merge kernel)
+// cost several microseconds.  Contexts are cut into chunks only to put WG_TARGET workgroups on
+// the chip when sequences x kv heads are fewer, or to keep a workgroup below TPC_MAX tiles;
+// never into chunks shorter than TPC_MIN tiles.
+constexpr int WG_TARGET = 512;           // two workgroups per CU
+constexpr int TPC_MAX = 256;             // 8192 keys
+constexpr int TPC_MIN = 16;              // 512 keys
 constexpr int PART_HDR = 32;             // floats in front of a partial result: 16 maxima, 16 sums
 
 template <int NW>
@@ -306,25 +314,44 @@ bool attn_decode_gqa_supported(int hq, int hkv, int hd) {
 #ifndef LS_ATTN_GQA_NW
 #define LS_ATTN_GQA_NW 4
 #endif
+namespace {
+// chunks per sequence for a launch of `rows` sequences whose longest context has `tiles` tiles
+int gqa_chunks(int rows, int hkv, int tiles) {
+  const int base = rows * hkv;
+  const int want = (WG_TARGET + base - 1) / base;
+  const int by_len = (tiles + TPC_MAX - 1) / TPC_MAX;
+  const int most = (tiles + TPC_MIN - 1) / TPC_MIN;
+  return std::max(1, std::min(std::max(want, by_len), most));
+}
+size_t gqa_part_bytes(int rows, int hq, int hkv, int nchunk) {
+  return (size_t)rows * hkv * nchunk * (PART_HDR + (size_t)(hq / hkv) * HD) * sizeof(float);
+}
+}  // namespace
+
+// An upper bound for every launch of at most `rows` sequences and `max_keys` keys: fewer rows
+// mean more chunks per sequence, but rows * hkv * chunks stays below WG_TARGET + rows * hkv
+// unless the length cap decides, which adds rows * hkv * chunks-by-length.
 size_t attn_decode_gqa_scratch_bytes(int rows, int hq, int hkv, int max_keys) {
   if (!attn_decode_gqa_supported(hq, hkv, HD)) return 0;
-  const int nchunk = ((max_keys + TK - 1) / TK + TPC - 1) / TPC;
-  if (nchunk <= 1) return 0;
-  return (size_t)rows * hkv * nchunk * (PART_HDR + (size_t)(hq / hkv) * HD) * sizeof(float);
+  const int tiles = (std::max(max_keys, 1) + TK - 1) / TK;
+  if (tiles <= TPC_MIN) return 0;
+  const int by_len = (tiles + TPC_MAX - 1) / TPC_MAX;
+  const size_t slots = (size_t)WG_TARGET + (size_t)rows * hkv * (1 + by_len);
+  return slots * (PART_HDR + (size_t)(hq / hkv) * HD) * sizeof(float);
 }
 
 void launch_attn_decode_gqa(const void* qkv, int qkv_stride, const float* cs_table, void* kc, void* vc,
                             const int32_t* row_seq, const int32_t* row_pos, int rows, int hq, int hkv, int max_seq,
                             void* out, hipStream_t st, int max_keys, float* scratch, size_t scratch_bytes) {
   if (rows <= 0) return;
-  // chunks of TPC tiles up to the longest context the caller vouches for; without scratch for
-  // their partial results every sequence stays one workgroup (one chunk as long as the cache)
+  // chunks up to the longest context the caller vouches for; without scratch for their
+  // partial results every sequence stays one workgroup (one chunk as long as the cache)
   const int tiles = (min(max(max_keys, 1), max_seq) + TK - 1) / TK;
-  int tpc = TPC, nchunk = (tiles + TPC - 1) / TPC;
-  if (nchunk > 1 && (!scratch || attn_decode_gqa_scratch_bytes(rows, hq, hkv, max_keys) > scratch_bytes)) {
-    tpc = (max_seq + TK - 1) / TK;
-    nchunk = 1;
-  }
+  int nchunk = gqa_chunks(rows, hkv, tiles);
+  int tpc = (tiles + nchunk - 1) / nchunk;
+  nchunk = (tiles + tpc - 1) / tpc;
+  if (nchunk > 1 && (!scratch || gqa_part_bytes(rows, hq, hkv, nchunk) > scratch_bytes)) nchunk = 1;
+  if (nchunk == 1) tpc = (max_seq + TK - 1) / TK;
   launch_nw<LS_ATTN_GQA_NW>(qkv, qkv_stride, cs_table, kc, vc, row_seq, row_pos, rows, hq, hkv, max_seq, out, st, scratch,
                             nchunk, tpc);
 }
