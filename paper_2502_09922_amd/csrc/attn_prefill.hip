@@ -40,7 +40,7 @@ template <int HD>
 __global__ void __launch_bounds__(256, 2)
 k_attn_prefill(const bf16* __restrict__ qkv, int qkv_stride, const bf16* __restrict__ kc,
                const bf16* __restrict__ vc, const int32_t* __restrict__ cu, int hq, int hkv, int max_seq,
-               bf16* __restrict__ out) {
+               bf16* __restrict__ out, int nq, int batch) {
   constexpr int ROWB = HD * 2;            // bytes per K / V row
   constexpr int CPR = HD / 8;             // 16-byte chunks per row: 16 or 8
   constexpr int TILE = BKV * ROWB;        // one K or V tile
@@ -53,13 +53,31 @@ k_attn_prefill(const bf16* __restrict__ qkv, int qkv_stride, const bf16* __restr
   typedef short s16x4 __attribute__((ext_vector_type(4)));
   typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 
-  const int b = blockIdx.z, h = blockIdx.y;
+  // Workgroup id -> (sequence, head, query tile).  All query tiles of all heads that share one
+  // (sequence, kv head) read the same keys and values, several times over (a causal prefix
+  // each).  Workgroup ids congruent modulo 8 run on the same XCD, so the nq * G workgroups of
+  // such a group get ids that are 8 apart: they run side by side behind one L2 and the group's
+  // keys and values come from memory once (with consecutive ids, the eight query tiles of a
+  // head ran on eight XCDs and each fetched its own copy: 2.5 x the algorithmic bytes).
+  // Within a group: longest query tiles first, the G heads of a tile next to each other.
+  const int G = hq / hkv;
+  const int ngroup = batch * hkv;
+  int grp, t;
+  if ((ngroup & 7) == 0) {
+    const int j = blockIdx.x >> 3;
+    t = j % (nq * G);
+    grp = (j / (nq * G)) * 8 + (blockIdx.x & 7);
+  } else {
+    t = blockIdx.x % (nq * G);
+    grp = blockIdx.x / (nq * G);
+  }
+  const int b = grp / hkv, kh = grp % hkv;
+  const int h = kh * G + t % G;
   const int row0 = cu[b], len = cu[b + 1] - row0;
   const int ntile = (len + BQ - 1) / BQ;
-  const int qt = ntile - 1 - (int)blockIdx.x;  // longest tiles first
+  const int qt = ntile - 1 - t / G;  // longest tiles first
   if (qt < 0) return;
   const int q0 = qt * BQ;
-  const int kh = h / (hq / hkv);
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // in a scalar register: what depends on it is wave-uniform
   const int lr = lane & 31, lh = lane >> 5;
@@ -237,13 +255,14 @@ bool attn_prefill_supported(int hq, int hkv, int hd) { return (hd == 128 || hd =
 void launch_attn_prefill(const void* qkv, int qkv_stride, const void* kc, const void* vc, const int32_t* cu_seqlens,
                          int batch, int max_len, int hq, int hkv, int hd, int max_seq, void* out, hipStream_t st) {
   if (batch <= 0 || max_len <= 0) return;
-  dim3 grid((max_len + BQ - 1) / BQ, hq, batch);
+  const int nq = (max_len + BQ - 1) / BQ;
+  dim3 grid((unsigned)nq * hq * batch);
   if (hd == 128)
     k_attn_prefill<128><<<grid, 256, 0, st>>>((const bf16*)qkv, qkv_stride, (const bf16*)kc, (const bf16*)vc,
-                                              cu_seqlens, hq, hkv, max_seq, (bf16*)out);
+                                              cu_seqlens, hq, hkv, max_seq, (bf16*)out, nq, batch);
   else
     k_attn_prefill<64><<<grid, 256, 0, st>>>((const bf16*)qkv, qkv_stride, (const bf16*)kc, (const bf16*)vc,
-                                             cu_seqlens, hq, hkv, max_seq, (bf16*)out);
+                                             cu_seqlens, hq, hkv, max_seq, (bf16*)out, nq, batch);
 }
 
 }  // namespace ls
