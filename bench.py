@@ -181,10 +181,11 @@ def run_throughput(name, steps, warmup, probes=True, peaks=False, decode_steps=N
         sink = torch.zeros(4, dtype=torch.float32, device="cuda")
         n = min(st.slab.numel(), 4 << 30)
         peak_read = B.ls_probe_read_gbps(ctypes.c_void_p(st.slab.data_ptr()), n, 3, ctypes.c_void_p(sink.data_ptr()), cur)
-        peak_mfma = B.ls_probe_mfma_tflops(2000, 3, ctypes.c_void_p(sink.data_ptr()), cur)
+        # 50000 iterations are about 7 ms: the rate the chip sustains under its power limit, not a burst
+        peak_mfma = B.ls_probe_mfma_tflops(50000, 3, ctypes.c_void_p(sink.data_ptr()), cur)
         assert peak_read > 0 and peak_mfma > 0, B.ls_last_error()
         out["measured_peaks"] = {"read_gbytes_per_s": peak_read, "mfma_bf16_tflops": peak_mfma,
-                                 "how": "ls_probe_read_gbps over 4 GiB of the resident weight slab, ls_probe_mfma_tflops (register-only loop)"}
+                                 "how": "ls_probe_read_gbps over 4 GiB of the resident weight slab, ls_probe_mfma_tflops (register-only loop of the prompt GEMM's MFMA instruction, varied operands, about 7 ms per repetition)"}
 
     chain = st.first and st.last  # a whole model: every decode step consumes the previous step's tokens
     out_dec = [(torch.empty(batch, dtype=torch.int32, device="cuda") if st.last

@@ -431,8 +431,11 @@ int ls_stage_probe_is_kernel_exact(const ls_stage* stage);
  * ls_probe_read_gbps: streams `bytes` (>= 16, a multiple of 16 is used) of the device buffer
  *   `buf` (16-byte aligned, only read) with the 16-byte non-temporal loads of the decode
  *   kernels, `reps` times after a warm-up; returns the GB/s of the fastest repetition.
- * ls_probe_mfma_tflops: every SIMD runs `iters` x 8 independent v_mfma_f32_32x32x16_bf16 from
- *   registers; returns the dense bf16 TFLOP/s of the fastest of `reps` repetitions.
+ * ls_probe_mfma_tflops: every SIMD runs `iters` x 16 independent v_mfma_f32_16x16x32_bf16 from
+ *   registers, with operands that differ from lane to lane; returns the dense bf16 TFLOP/s of
+ *   the fastest of `reps` repetitions.  The rate depends on how long the loop runs: the chip
+ *   holds its top clock for a few hundred microseconds (`iters` of a few thousand) and settles
+ *   at what its power limit allows over milliseconds (`iters` of 50000 is about 7 ms).
  * `sink` is a device pointer to at least 4 writable bytes or NULL (the kernels never write it
  * in practice; it keeps their work from being optimised away).  Both block until done and
  * return a negative value on bad arguments or a HIP error (see ls_last_error).

@@ -2,8 +2,10 @@
 // resources the path is bound by, measured with the same instructions the kernels use.
 //   * a streaming read of a device buffer with 16-byte non-temporal loads, as the decode
 //     kernels read weights and cached keys / values;
-//   * a register-only loop of v_mfma_f32_32x32x16_bf16 on every SIMD, as the prompt GEMM
-//     issues them, with no operand traffic at all.
+//   * a register-only loop of v_mfma_f32_16x16x32_bf16 on every SIMD, the instruction the
+//     prompt GEMM issues, with no operand traffic at all and with operands that differ from
+//     lane to lane (dense MFMA work is power-bound on this chip and all-zero or constant
+//     operands let it hold a clock that real data does not: 2.4 GHz against about 2.15).
 // bench.py reports its fractions against the published peaks and against these.
 #include "../../include/ls_stage.h"
 #include "kernels.hpp"
@@ -35,24 +37,22 @@ __global__ void __launch_bounds__(256) k_probe_read(const ls::u32x4* __restrict_
 }
 
 __global__ void __launch_bounds__(256) k_probe_mfma(int iters, float seed, float* sink) {
-  ls::f32x16 acc[8];
+  ls::f32x4 acc[16];
 #pragma unroll
-  for (int j = 0; j < 8; ++j)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
+  for (int j = 0; j < 16; ++j) acc[j] = ls::f32x4{0.f, 0.f, 0.f, 0.f};
   ls::bf16x8 a, b;
 #pragma unroll
   for (int e = 0; e < 8; ++e) {
-    a[e] = (ls::bf16)(seed + (float)(threadIdx.x & 7));
-    b[e] = (ls::bf16)(seed * (float)(e + 1));
+    a[e] = (ls::bf16)(seed + (float)((threadIdx.x * 7 + e * 13) % 31) * 0.03f - 0.4f);
+    b[e] = (ls::bf16)(seed + (float)((threadIdx.x * 5 + e * 11) % 29) * 0.02f - 0.3f);
   }
   for (int it = 0; it < iters; ++it) {
 #pragma unroll
-    for (int j = 0; j < 8; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[j], 0, 0, 0);
+    for (int j = 0; j < 16; ++j) acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, acc[j], 0, 0, 0);
   }
   float s = 0.f;
 #pragma unroll
-  for (int j = 0; j < 8; ++j) s += acc[j][0] + acc[j][15];
+  for (int j = 0; j < 16; ++j) s += acc[j][0] + acc[j][3];
   if (sink && s == 12345.678f) sink[0] = s;  // keeps the accumulators alive
 }
 
@@ -114,7 +114,7 @@ double ls_probe_mfma_tflops(int iters, int reps, void* sink, void* hip_stream) {
     ls::set_last_error("ls_probe_mfma_tflops: HIP error");
     return -1.0;
   }
-  const double flops = (double)MFMA_WGS * 4 /*waves*/ * iters * 8 * (2.0 * 32 * 32 * 16);
+  const double flops = (double)MFMA_WGS * 4 /*waves*/ * iters * 16 * (2.0 * 16 * 16 * 32);
   return flops / (ms * 1e-3) / 1e12;
 }
 
