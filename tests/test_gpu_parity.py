@@ -113,6 +113,25 @@ def test_grouped_query_decode_with_contexts_of_128_and_2048_in_one_batch():
     gpu.close()
 
 
+def test_prompt_gemm_edges_rows_and_columns_that_fill_no_whole_tile_or_vector():
+    """The prompt GEMM stores four consecutive columns per lane and works on 256 x 256 tiles:
+    a FFN width that is no multiple of four (the gate-up GEMM then takes its element-wise
+    store path, the down projection a K that is no multiple of 64), prompt rows that end inside
+    a tile, widths that end inside a 16-column MFMA tile."""
+    for ffn, d, lengths in ((690, 256, [70, 33, 1]), (1412, 384, [131, 200]), (700, 320, [257])):
+        shape = synth.StageShape("bf16", 2, d, d // 64, d // 64, 64, ffn, 0)
+        seed = 61
+        B, S = len(lengths), max(lengths)
+        gpu = make_gpu(shape, seed, 0, 2, B, S + 2, sum(lengths))
+        ora = make_oracle(shape, seed, 0, 2, B, S + 2)
+        x = synth.hidden_states(shape, seed + 1, sum(lengths))
+        tag = "d%d F%d T%d" % (d, ffn, sum(lengths))
+        check_close(to_host(gpu.prefill(to_dev(shape, x), lengths)), ora.prefill(x, lengths), "bf16", tag + " prompt")
+        xs = synth.hidden_states(shape, seed + 2, B)
+        check_close(to_host(gpu.decode(to_dev(shape, xs), B, S)), ora.decode(xs), "bf16", tag + " step")
+        gpu.close()
+
+
 def test_split_stages_equal_whole_stage():
     """Running layers [0,k) then [k,L) as two stages equals one stage [0,L)."""
     shape, seed, lengths = MINI_BF16.with_(vocab=0), 5, [33, 8]
