@@ -38,7 +38,9 @@ namespace {
 constexpr int waves_for(int g) { return g == 1 ? LS_ATTN_NW1 : LS_ATTN_NW; }
 
 template <int HD, int G>
-__global__ void __launch_bounds__(waves_for(G) * 64)
+// with one query head per kv head the kernel fits 64 registers: eight wavefronts per SIMD, two
+// 16-wavefront workgroups per CU
+__global__ void __launch_bounds__(waves_for(G) * 64, (G == 1 ? 8 : 1))
 k_attn_decode(const bf16* __restrict__ qkv, int qkv_stride, const float2* __restrict__ cs,
               bf16* __restrict__ kc, bf16* __restrict__ vc, const int32_t* __restrict__ row_seq,
               const int32_t* __restrict__ row_pos, int hq, int hkv, int max_seq, bf16* __restrict__ out) {
@@ -107,6 +109,28 @@ k_attn_decode(const bf16* __restrict__ qkv, int qkv_stride, const float2* __rest
     m[g] = mn_;                                                                              \
   }
 
+  // the new row first (wave 0): rotate k, round both to bf16, append to the cache, attend to
+  // it.  Done before the cache stream so that the rotation table is dead inside the loop.
+  if (wave == 0) {
+    const bf16x8 kn = *reinterpret_cast<const bf16x8*>(row + (size_t)(hq + kh) * HD + dl * 8);
+    const bf16x8 vn = *reinterpret_cast<const bf16x8*>(row + (size_t)(hq + hkv + kh) * HD + dl * 8);
+    bf16x8 kr;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const float u0 = (float)kn[2 * i], u1 = (float)kn[2 * i + 1];
+      kr[2 * i] = (bf16)(u0 * rot[i].x - u1 * rot[i].y);
+      kr[2 * i + 1] = (bf16)(u0 * rot[i].y + u1 * rot[i].x);
+    }
+    if (slot == 0) {
+      *reinterpret_cast<bf16x8*>(kb + (size_t)pos * HD + dl * 8) = kr;
+      *reinterpret_cast<bf16x8*>(vb + (size_t)pos * HD + dl * 8) = vn;
+    }
+    float kx[8], vx[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { kx[e] = (float)kr[e]; vx[e] = (float)vn[e]; }
+    const bool valid = slot == 0;
+    LS_KEY_UPDATE(kx, vx, valid)
+  }
   // the cache is read once per step: non-temporal loads.  The cache stream is software pipelined: the loads of the next group of U*KPI keys are
   // in flight while the current group is folded into the softmax state; a load whose keys
   // all lie past the wave's range is not issued at all
@@ -144,27 +168,6 @@ k_attn_decode(const bf16* __restrict__ qkv, int qkv_stride, const float2* __rest
 #undef LS_LOAD_GROUP
 #undef LS_FOLD_GROUP
 
-  // the new row: rotate k, round both to bf16, append to the cache, attend to it
-  if (wave == 0) {
-    const bf16x8 kn = *reinterpret_cast<const bf16x8*>(row + (size_t)(hq + kh) * HD + dl * 8);
-    const bf16x8 vn = *reinterpret_cast<const bf16x8*>(row + (size_t)(hq + hkv + kh) * HD + dl * 8);
-    bf16x8 kr;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const float u0 = (float)kn[2 * i], u1 = (float)kn[2 * i + 1];
-      kr[2 * i] = (bf16)(u0 * rot[i].x - u1 * rot[i].y);
-      kr[2 * i + 1] = (bf16)(u0 * rot[i].y + u1 * rot[i].x);
-    }
-    if (slot == 0) {
-      *reinterpret_cast<bf16x8*>(kb + (size_t)pos * HD + dl * 8) = kr;
-      *reinterpret_cast<bf16x8*>(vb + (size_t)pos * HD + dl * 8) = vn;
-    }
-    float kx[8], vx[8];
-#pragma unroll
-    for (int e = 0; e < 8; ++e) { kx[e] = (float)kr[e]; vx[e] = (float)vn[e]; }
-    const bool valid = slot == 0;
-    LS_KEY_UPDATE(kx, vx, valid)
-  }
 #undef LS_KEY_UPDATE
 
   // merge the key slots of the wave (lanes that hold the same dimensions)
