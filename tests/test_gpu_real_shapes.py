@@ -249,6 +249,27 @@ def test_streamed_equals_preloaded_at_the_real_7b_layer_size():
     st.close()
 
 
+def test_the_prompt_pass_is_bit_identical_from_run_to_run():
+    """The prompt GEMM hands its LDS stages over with waits that leave loads in flight (all
+    fills but the youngest prefetch; exact counts of younger LDS reads), the attention kernel
+    shares keys through an L2: a wait that is one too loose would show as a result that
+    depends on timing.  Twenty prompt passes of two 7B-shaped layers over 8 x 512 rows, and of
+    two 13B-shaped layers over 8 x 1024 rows, must equal the first bit for bit."""
+    import torch
+
+    for key, B, S in (("llama7b", 8, 512), ("llama13b", 8, 1024)):
+        shape, seed, lo, hi = synth.CONFIGS[key].with_(vocab=0), 1234, 8, 10
+        gpu = gpu_stage(shape, layers_of(shape, seed, lo, hi), lo, hi, B, S + 1, B * S)
+        x = to_dev(shape, synth.hidden_states(shape, seed + 1, B * S))
+        ref = gpu.prefill(x, [S] * B).clone()
+        ref_k = gpu.k.clone()
+        assert torch.isfinite(ref.float()).all()
+        for i in range(20):
+            got = gpu.prefill(x, [S] * B)
+            assert torch.equal(got, ref) and torch.equal(gpu.k, ref_k), (key, i)
+        gpu.close()
+
+
 def test_llama13b_whole_model_at_full_depth():
     """Configuration 3 at its full depth: embedding, all 40 layers, final norm and LM head at
     V = 32000 as ONE stage, on four short ragged prompts.
