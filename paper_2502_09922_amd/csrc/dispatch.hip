@@ -35,7 +35,7 @@ void launch_gemm(uint32_t dt, Epilogue epi, const void* A, const void* W, int M,
 void launch_attention_block(uint32_t dt, const int32_t* cu_seqlens, int batch, int max_len, void* qkv,
                             const float* cs_table, void* kcache, void* vcache, const int32_t* row_seq,
                             const int32_t* row_pos, int rows, int hq, int hkv, int hd, int max_seq, void* out,
-                            hipStream_t st, float* attn_scratch, size_t attn_scratch_bytes) {
+                            hipStream_t st, float* attn_scratch, size_t attn_scratch_bytes, bool rope_done) {
   const bool decode = cu_seqlens == nullptr;
   const int qkv_stride = (hq + 2 * hkv) * hd;
   if (dt == BF16 && decode && attn_decode_gqa_supported(hq, hkv, hd)) {
@@ -47,7 +47,7 @@ void launch_attention_block(uint32_t dt, const int32_t* cu_seqlens, int batch, i
     launch_attn_decode(qkv, qkv_stride, cs_table, kcache, vcache, row_seq, row_pos, rows, hq, hkv, hd, max_seq, out, st);
     return;
   }
-  launch_rope_append(dt, qkv, cs_table, row_seq, row_pos, rows, hq, hkv, hd, max_seq, kcache, vcache, st);
+  if (!rope_done) launch_rope_append(dt, qkv, cs_table, row_seq, row_pos, rows, hq, hkv, hd, max_seq, kcache, vcache, st);
   if (dt == BF16 && !decode && attn_prefill_supported(hq, hkv, hd)) {
     launch_attn_prefill(qkv, qkv_stride, kcache, vcache, cu_seqlens, batch, max_len, hq, hkv, hd, max_seq, out, st);
     return;

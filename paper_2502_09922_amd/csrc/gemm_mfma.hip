@@ -100,10 +100,12 @@ __device__ __forceinline__ TileAt tile_at(int l, int tiles_m, int tiles_n) {
   return t;
 }
 
+constexpr int EPI_ROPE = 4;  // EPI_STORE with RoPE and the KV-cache append (QKV projection of a prompt pass)
+
 template <int EPI>
 __global__ void __launch_bounds__(NWAVE * 64, 1)
 k_gemm_mfma(const bf16* __restrict__ A, const bf16* __restrict__ W, int M, int N, int K,
-              void* __restrict__ outv, float* __restrict__ resid, int tiles_m, int tiles_n) {
+            void* __restrict__ outv, float* __restrict__ resid, int tiles_m, int tiles_n, RopeAppend rp) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   typedef __attribute__((address_space(3))) void lds_void;
   constexpr bool GLU = (EPI == EPI_SWIGLU);
@@ -334,6 +336,63 @@ k_gemm_mfma(const bf16* __restrict__ A, const bf16* __restrict__ W, int M, int N
 
   // ---- epilogue: acc[i][j][r] is C[m0 + 128 wm + 16 i + lane%16][n0 + 64 wn + 16 j + 4 (lane/16) + r]
   const bool vec = (N & 3) == 0;
+  if constexpr (EPI == EPI_ROPE) {
+    // A wavefront's 64 columns lie inside one head (head_dim 64 or 128): query, key or value.
+    // A lane's four consecutive columns are two rotation pairs (dims 2p, 2p+1); their
+    // (cos, sin) are one 16-byte table load.  The table loads of the next row block are in
+    // flight while the current one is rotated and stored.
+    const int ncol0 = n0 + wn * 64;
+    if (ncol0 >= N) return;  // N is a multiple of the head size: the whole wavefront is out
+    const int head = ncol0 / rp.hd, dd0 = ncol0 - head * rp.hd;
+    const bool is_q = head < rp.hq, is_v = head >= rp.hq + rp.hkv;
+    const int kh = is_v ? head - rp.hq - rp.hkv : head - rp.hq;
+    int pos[8], seq[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int m = m0 + wm * 128 + i * 16 + l16;
+      pos[i] = m < M ? rp.row_pos[m] : -1;
+      seq[i] = (m < M && !is_q) ? rp.row_seq[m] : 0;
+    }
+    f32x4 tab[2][4];
+#define LS_TAB_LOAD(i_, set_)                                                                         \
+  if (!is_v) {                                                                                        \
+    _Pragma("unroll") for (int j = 0; j < 4; ++j)                                                     \
+      tab[set_][j] = *reinterpret_cast<const f32x4*>(                                                 \
+          rp.cs + ((size_t)max(pos[i_], 0) * (rp.hd >> 1) + ((dd0 + j * 16 + 4 * lq) >> 1)) * 2);     \
+  }
+    LS_TAB_LOAD(0, 0)
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      if (i + 1 < 8) LS_TAB_LOAD(i + 1, (i + 1) & 1)
+      const int m = m0 + wm * 128 + i * 16 + l16;
+      // a row past the end of the call stores nothing; a row whose sequence has no room left
+      // keeps its query as projected and appends nothing, as with the separate rotation kernel
+      if (m >= M || (pos[i] < 0 && !is_q)) continue;
+      const bool turn = !is_v && pos[i] >= 0;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int dd = dd0 + j * 16 + 4 * lq;
+        f32x4 v = acc[i][j];
+        if (turn) {
+          const f32x4 t = tab[i & 1][j];  // cos, sin of pair dd/2; cos, sin of pair dd/2 + 1
+          // the projection's output is rounded to bf16 first, as the separate rotation kernel sees it
+          const float u0 = (float)(bf16)v[0], u1 = (float)(bf16)v[1], u2 = (float)(bf16)v[2], u3 = (float)(bf16)v[3];
+          v[0] = u0 * t[0] - u1 * t[1];
+          v[1] = u0 * t[1] + u1 * t[0];
+          v[2] = u2 * t[2] - u3 * t[3];
+          v[3] = u2 * t[3] + u3 * t[2];
+        }
+        bf16x4 y;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) y[r] = (bf16)v[r];
+        bf16* p = is_q ? (bf16*)outv + (size_t)m * N + ncol0 + j * 16 + 4 * lq
+                       : (is_v ? rp.vc : rp.kc) + (((size_t)seq[i] * rp.hkv + kh) * rp.max_seq + pos[i]) * rp.hd + dd;
+        *reinterpret_cast<bf16x4*>(p) = y;
+      }
+    }
+#undef LS_TAB_LOAD
+    return;
+  }
   if constexpr (EPI == EPI_RESID) {
     // fp32 read-modify-write of the residual rows, 16 bytes per lane; the eight old values of
     // two row blocks are requested before the first sum is stored
@@ -415,7 +474,8 @@ k_gemm_mfma(const bf16* __restrict__ A, const bf16* __restrict__ W, int M, int N
 }
 
 template <int EPI>
-void launch_t(const void* A, const void* W, int M, int N, int K, void* out, float* resid, hipStream_t st) {
+void launch_t(const void* A, const void* W, int M, int N, int K, void* out, float* resid, hipStream_t st,
+              const RopeAppend& rope = RopeAppend{}) {
   static std::atomic<uint64_t> lds_allowed{0};
   constexpr int LDS_BYTES = SMEM_BYTES + 256;  // + the scratch words of the L2 prefetch
   allow_dynamic_lds((const void*)k_gemm_mfma<EPI>, LDS_BYTES, lds_allowed);
@@ -425,12 +485,21 @@ void launch_t(const void* A, const void* W, int M, int N, int K, void* out, floa
   const int nt = tiles_m * tiles_n;
   const int grid = ((nt + 255) / 256) * 256;
   launch_kernel(k_gemm_mfma<EPI>, dim3(grid), dim3(NWAVE * 64), LDS_BYTES, st, (const bf16*)A, (const bf16*)W, M, N,
-                K, out, resid, tiles_m, tiles_n);
+                K, out, resid, tiles_m, tiles_n, rope);
 }
 
 }  // namespace
 
 bool gemm_mfma_supported(int M, int N, int K) { return M >= 1 && N >= 1 && K >= 2 * BK && K % BK == 0; }
+
+bool gemm_mfma_rope_supported(int M, int N, int K, int hq, int hkv, int hd) {
+  return gemm_mfma_supported(M, N, K) && (hd == 64 || hd == 128) && N == (hq + 2 * hkv) * hd;
+}
+
+void launch_gemm_mfma_rope(const void* A, const void* W, int M, int N, int K, void* out, const RopeAppend& rope,
+                           hipStream_t st) {
+  launch_t<EPI_ROPE>(A, W, M, N, K, out, nullptr, st, rope);
+}
 
 void launch_gemm_mfma(Epilogue epi, const void* A, const void* W, int M, int N, int K, void* out, float* resid,
                         hipStream_t st) {

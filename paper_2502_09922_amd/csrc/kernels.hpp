@@ -79,6 +79,21 @@ void launch_gemm_generic(uint32_t dt, Epilogue epi, const void* A, const void* W
 bool gemm_mfma_supported(int M, int N, int K);
 void launch_gemm_mfma(Epilogue epi, const void* A, const void* W, int M, int N, int K, void* out, float* resid,
                       hipStream_t st);
+// The QKV projection of a prompt pass with RoPE and the KV-cache append in its epilogue: rotated
+// query rows go to out[M,N] (N = (hq + 2 hkv) hd, key and value columns of `out` are not
+// written), rotated keys and the values go to their cache rows (row_seq[m], row_pos[m]; rows
+// with row_pos < 0 are skipped).  head_dim 64 or 128.
+struct RopeAppend {
+  const float* cs = nullptr;        // cos/sin table [max_seq][hd/2][2]
+  const int32_t* row_seq = nullptr;
+  const int32_t* row_pos = nullptr;
+  int hq = 0, hkv = 0, hd = 0, max_seq = 0;
+  __bf16* kc = nullptr;
+  __bf16* vc = nullptr;
+};
+bool gemm_mfma_rope_supported(int M, int N, int K, int hq, int hkv, int hd);
+void launch_gemm_mfma_rope(const void* A, const void* W, int M, int N, int K, void* out, const RopeAppend& rope,
+                           hipStream_t st);
 
 // bf16 weight-streaming kernel for decode steps (M <= 64); needs N % 16 == 0, K % 128 == 0.
 // ks = wavefronts that split K inside a workgroup (4, 8, 16), 0 = chosen from the shape.
@@ -127,7 +142,8 @@ void launch_rope_append(uint32_t dt, void* qkv, const float* cs_table, const int
 void launch_attention_block(uint32_t dt, const int32_t* cu_seqlens, int batch, int max_len, void* qkv,
                             const float* cs_table, void* kcache, void* vcache, const int32_t* row_seq,
                             const int32_t* row_pos, int rows, int hq, int hkv, int hd, int max_seq, void* out,
-                            hipStream_t st, float* attn_scratch = nullptr, size_t attn_scratch_bytes = 0);
+                            hipStream_t st, float* attn_scratch = nullptr, size_t attn_scratch_bytes = 0,
+                            bool rope_done = false);
 
 // bf16 split-KV decode attention fused with RoPE and the cache append; head_dim 64 or 128,
 // Hq/Hkv in {1,2,4,8}.

@@ -640,9 +640,20 @@ ls_status forward(ls_stage* s, bool prefill, const void* in, const int32_t* cu_d
     char* vc = (char*)kv->v + li * kv_layer;
 
     PROBE(LS_OP_NORM, launch_rmsnorm(dt, x, base + sp[0].off, y, rows, d, c.rms_eps, nullptr, st));
-    PROBE(LS_OP_GEMM_QKV, launch_gemm(dt, EPI_STORE, y, base + sp[1].off, rows, qkv_cols, d, qkv, nullptr, st, &gsc));
+    // many-row prompt passes: RoPE and the cache append ride in the QKV projection's epilogue
+    const bool rope_in_gemm = prefill && dt == BF16 && rows > 64 && attn_prefill_supported(hq, hkv, hd) &&
+                              gemm_mfma_rope_supported(rows, qkv_cols, d, hq, hkv, hd);
+    if (rope_in_gemm) {
+      RopeAppend ra;
+      ra.cs = cs; ra.row_seq = row_seq; ra.row_pos = row_pos;
+      ra.hq = hq; ra.hkv = hkv; ra.hd = hd; ra.max_seq = c.max_seq;
+      ra.kc = (__bf16*)kc; ra.vc = (__bf16*)vc;
+      PROBE(LS_OP_GEMM_QKV, launch_gemm_mfma_rope(y, base + sp[1].off, rows, qkv_cols, d, qkv, ra, st));
+    } else {
+      PROBE(LS_OP_GEMM_QKV, launch_gemm(dt, EPI_STORE, y, base + sp[1].off, rows, qkv_cols, d, qkv, nullptr, st, &gsc));
+    }
     PROBE(LS_OP_ATTENTION, launch_attention_block(dt, cu_dev, batch, max_len, qkv, cs, kc, vc, row_seq, row_pos, rows,
-                                                  hq, hkv, hd, c.max_seq, attn, st));
+                                                  hq, hkv, hd, c.max_seq, attn, st, nullptr, 0, rope_in_gemm));
     PROBE(LS_OP_GEMM_O, launch_gemm(dt, EPI_RESID, attn, base + sp[2].off, rows, d, hq * hd, nullptr, x, st, &gsc));
     launch_rmsnorm(dt, x, base + sp[3].off, y, rows, d, c.rms_eps, nullptr, st);
     PROBE(LS_OP_GEMM_GATEUP, launch_gemm(dt, EPI_SWIGLU, y, base + sp[4].off, rows, F, d, hbuf, nullptr, st, &gsc));
