@@ -100,6 +100,36 @@ __device__ __forceinline__ TileAt tile_at(int l, int tiles_m, int tiles_n) {
   return t;
 }
 
+// Two result fragments that lie side by side (16 + 16 columns of the same 16 rows), as four
+// bf16 values per lane each -> eight consecutive columns per lane: lane (row, q) ends up with
+// columns 8q..8q+7 of the 32, so that the four lanes of a row store 64 contiguous bytes with
+// one 16-byte store each instead of 4 x 8 bytes twice (a store instruction is sixteen row
+// segments for the memory pipeline whatever their width: half the instructions, half the
+// requests).  The data moves between the wavefront's four 16-lane rows with the two swap
+// instructions of this chip: v_permlane32_swap exchanges rows 2,3 of its first operand with rows
+// 0,1 of its second, v_permlane16_swap rows 1,3 of the first with rows 0,2 of the second.
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ u32x4 side_by_side(bf16x4 a, bf16x4 b) {
+  const u32x2 ua = __builtin_bit_cast(u32x2, a), ub = __builtin_bit_cast(u32x2, b);
+  u32x4 o;
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    // rows after the first swap: first = a0 a1 b0 b1, second = a2 a3 b2 b3 (a2: a's value in row 2)
+    const u32x2 s = __builtin_amdgcn_permlane32_swap(ua[h], ub[h], false, false);
+    // after the second: first = a0 a2 b0 b2, second = a1 a3 b1 b3
+    const u32x2 t = __builtin_amdgcn_permlane16_swap(s[0], s[1], false, false);
+    o[h] = t[0];      // columns 8q + 2h, +1: from the fragment's row 2(q%2)
+    o[2 + h] = t[1];  // columns 8q + 4 + 2h, +1: from row 2(q%2) + 1
+  }
+  return o;
+}
+__device__ __forceinline__ bf16x4 to_bf16x4(f32x4 v) {
+  bf16x4 y;
+#pragma unroll
+  for (int r = 0; r < 4; ++r) y[r] = (bf16)v[r];
+  return y;
+}
+
 constexpr int EPI_ROPE = 4;  // EPI_STORE with RoPE and the KV-cache append (QKV projection of a prompt pass)
 
 template <int EPI>
@@ -367,11 +397,11 @@ k_gemm_mfma(const bf16* __restrict__ A, const bf16* __restrict__ W, int M, int N
       const int m = m0 + wm * 128 + i * 16 + l16;
       // a row past the end of the call stores nothing; a row whose sequence has no room left
       // keeps its query as projected and appends nothing, as with the separate rotation kernel
-      if (m >= M || (pos[i] < 0 && !is_q)) continue;
+      const bool live = m < M && (pos[i] >= 0 || is_q);
       const bool turn = !is_v && pos[i] >= 0;
+      bf16x4 y[4];
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
-        const int dd = dd0 + j * 16 + 4 * lq;
         f32x4 v = acc[i][j];
         if (turn) {
           const f32x4 t = tab[i & 1][j];  // cos, sin of pair dd/2; cos, sin of pair dd/2 + 1
@@ -382,25 +412,29 @@ k_gemm_mfma(const bf16* __restrict__ A, const bf16* __restrict__ W, int M, int N
           v[2] = u2 * t[2] - u3 * t[3];
           v[3] = u2 * t[3] + u3 * t[2];
         }
-        bf16x4 y;
+        y[j] = to_bf16x4(v);
+      }
+      bf16* row = is_q ? (bf16*)outv + (size_t)m * N + ncol0
+                       : (is_v ? rp.vc : rp.kc) + (((size_t)seq[i] * rp.hkv + kh) * rp.max_seq + max(pos[i], 0)) * rp.hd + dd0;
 #pragma unroll
-        for (int r = 0; r < 4; ++r) y[r] = (bf16)v[r];
-        bf16* p = is_q ? (bf16*)outv + (size_t)m * N + ncol0 + j * 16 + 4 * lq
-                       : (is_v ? rp.vc : rp.kc) + (((size_t)seq[i] * rp.hkv + kh) * rp.max_seq + pos[i]) * rp.hd + dd;
-        *reinterpret_cast<bf16x4*>(p) = y;
+      for (int jp = 0; jp < 2; ++jp) {
+        const u32x4 o = side_by_side(y[2 * jp], y[2 * jp + 1]);  // every lane takes part
+        if (live) *reinterpret_cast<u32x4*>(row + jp * 32 + 8 * lq) = o;
       }
     }
 #undef LS_TAB_LOAD
     return;
   }
   if constexpr (EPI == EPI_RESID) {
-    // fp32 read-modify-write of the residual rows, 16 bytes per lane; the eight old values of
-    // two row blocks are requested before the first sum is stored
+    // fp32 read-modify-write of the residual rows, 16 bytes per lane; the sixteen old values of
+    // four row blocks are requested before the first sum is stored (the operand fragments'
+    // registers are free by now)
+    constexpr int RB = 4;
 #pragma unroll
-    for (int i2 = 0; i2 < 8; i2 += 2) {
-      f32x4 old[2][4];
+    for (int i2 = 0; i2 < 8; i2 += RB) {
+      f32x4 old[RB][4];
 #pragma unroll
-      for (int ii = 0; ii < 2; ++ii)
+      for (int ii = 0; ii < RB; ++ii)
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
           const int m = m0 + wm * 128 + (i2 + ii) * 16 + l16;
@@ -412,7 +446,7 @@ k_gemm_mfma(const bf16* __restrict__ A, const bf16* __restrict__ W, int M, int N
             for (int r = 0; r < 4; ++r) old[ii][j][r] = (m < M && n + r < N) ? p[r] : 0.f;
         }
 #pragma unroll
-      for (int ii = 0; ii < 2; ++ii)
+      for (int ii = 0; ii < RB; ++ii)
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
           const int m = m0 + wm * 128 + (i2 + ii) * 16 + l16;
@@ -427,6 +461,35 @@ k_gemm_mfma(const bf16* __restrict__ A, const bf16* __restrict__ W, int M, int N
         }
     }
     return;
+  }
+  if constexpr (EPI == EPI_STORE || GLU) {
+    // bf16 results, the wavefront's columns all inside the matrix and rows 16-byte aligned:
+    // 16-byte stores of eight consecutive columns (see side_by_side)
+    constexpr int WCOLS = GLU ? 32 : 64;
+    const int ncol0 = n0 + wn * WCOLS;
+    if ((N & 7) == 0 && ncol0 + WCOLS <= N) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const int m = m0 + wm * 128 + i * 16 + l16;
+        bf16* row = (bf16*)outv + (size_t)min(m, M - 1) * N + ncol0 + 8 * lq;
+        if constexpr (GLU) {
+          f32x4 g[2];
+#pragma unroll
+          for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) g[j][r] = silu_f(acc[i][j][r]) * acc[i][j + 2][r];
+          const u32x4 o = side_by_side(to_bf16x4(g[0]), to_bf16x4(g[1]));
+          if (m < M) *reinterpret_cast<u32x4*>(row) = o;
+        } else {
+#pragma unroll
+          for (int jp = 0; jp < 2; ++jp) {
+            const u32x4 o = side_by_side(to_bf16x4(acc[i][2 * jp]), to_bf16x4(acc[i][2 * jp + 1]));
+            if (m < M) *reinterpret_cast<u32x4*>(row + jp * 32) = o;
+          }
+        }
+      }
+      return;
+    }
   }
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
