@@ -43,19 +43,31 @@
 // next stage's first fragments and issues the fills that refill the retired stage, one after
 // every fourth MFMA.
 //
-// What bounds it, from shader-clock stamps around the hand-over (development build): a k-step
-// takes about 2800 cycles at 2.0 GHz where its 256 MFMAs per SIMD need 2048.  On every SIMD
-// the older of the two wavefronts finishes its half of the work after about 1750 cycles, the
-// younger after about 2500; the barrier costs about 150.  Without any fills the same loop
+// Persistent workgroups: 256 workgroups, one per CU, each walking tiles l, l + 256, ...; a
+// workgroup's k-steps form ONE stream across its tiles.  The fills of a tile's last two
+// k-steps fetch the first two k-blocks of the workgroup's next tile, so the next tile's first
+// hand-over finds its data there, and the epilogue's stores drain while the next tile
+// computes.  Wall-clock stamps per tile (development build, 13B shapes) of the version that
+// launched one workgroup per tile: 2.2-2.5 us from a workgroup's start to its first hand-over
+// and 1.2 / 2.6 / 7.4 us (QKV / gate-up / residual GEMMs) between one workgroup's end and the
+// next one's start on the same CU, against 114 us of k-loop per tile at K = 5120; both are
+// gone (the residual GEMMs gained 2 %, gate-up 1.3 %, QKV 1 %).  What remains outside the
+// k-loop is the epilogue itself, with the matrix pipe idle: 3 us (SwiGLU), 9.5 us (RoPE and
+// cache append), 12 us (fp32 residual read-modify-write) per tile.
+//
+// What bounds the k-loop, from shader-clock stamps around the hand-over (development build): a
+// k-step takes about 2800 cycles at 2.0 GHz where its 256 MFMAs per SIMD need 2048.  On every
+// SIMD the older of the two wavefronts finishes its half of the work after about 1750 cycles,
+// the younger after about 2500; the barrier costs about 150.  Without any fills the same loop
 // takes about 2350 cycles at 2.3 GHz, and what the fills cost is power first (the clock), wall
 // time second: with fills whose lines all hit L2 the loop ran no faster, with a third fewer
 // LDS reads 2 % faster.  Fills that miss L2 did cost wall time until the prefetch below.
 //
-// Workgroup ids are remapped so that the 32 workgroups resident on one XCD (ids congruent
-// modulo 8 land on the same XCD) work on a 4 x 8 patch of neighbouring tiles and share their
-// operand panels through that XCD's L2, and so that the eight XCDs work on the eight patches
-// of one 16 x 16 block of tiles at the same time and find each other's panels in the
-// memory-side cache (+1.2 % over patches that are far apart).
+// Tile order: the 32 workgroups resident on one XCD (ids congruent modulo 8 land on the same
+// XCD) work on a 4 x 8 patch of neighbouring tiles and share their operand panels through that
+// XCD's L2, and the eight XCDs work on the eight patches of one 16 x 16 block of tiles at the
+// same time and find each other's panels in the memory-side cache (+1.2 % over patches that
+// are far apart).
 #include "kernels.hpp"
 #include "device_util.hpp"
 
@@ -70,6 +82,7 @@ constexpr int TILE_BYTES = BM * ROWB;      // 32 KB per operand tile
 constexpr int STAGE_BYTES = 2 * TILE_BYTES;
 constexpr int SMEM_BYTES = 2 * STAGE_BYTES;
 constexpr int FI = 4;                      // fill instructions per operand per wavefront and stage
+constexpr int PERSISTENT_WGS = 256;        // one workgroup per CU
 constexpr int PF_AHEAD = 1;                // k-steps between the L2 prefetch of a line and its fill
 
 __device__ __forceinline__ unsigned swz(int row, int chunk) {
@@ -123,6 +136,10 @@ __device__ __forceinline__ u32x4 side_by_side(bf16x4 a, bf16x4 b) {
   }
   return o;
 }
+// a where every bit of mask is set, b where none is (a select the compiler cannot turn into a branch)
+__device__ __forceinline__ float pick_bits(unsigned mask, float a, float b) {
+  return __uint_as_float((__float_as_uint(a) & mask) | (__float_as_uint(b) & ~mask));
+}
 __device__ __forceinline__ bf16x4 to_bf16x4(f32x4 v) {
   bf16x4 y;
 #pragma unroll
@@ -132,239 +149,12 @@ __device__ __forceinline__ bf16x4 to_bf16x4(f32x4 v) {
 
 constexpr int EPI_ROPE = 4;  // EPI_STORE with RoPE and the KV-cache append (QKV projection of a prompt pass)
 
+// Epilogue of one tile.  acc[i][j][r] is C[m0 + 128 wm + 16 i + lane%16][n0 + 64 wn + 16 j + 4 (lane/16) + r].
 template <int EPI>
-__global__ void __launch_bounds__(NWAVE * 64, 1)
-k_gemm_mfma(const bf16* __restrict__ A, const bf16* __restrict__ W, int M, int N, int K,
-            void* __restrict__ outv, float* __restrict__ resid, int tiles_m, int tiles_n, RopeAppend rp) {
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  typedef __attribute__((address_space(3))) void lds_void;
+__device__ __forceinline__ void store_tile(f32x4 (&acc)[8][4], int m0, int n0, int M, int N, void* __restrict__ outv,
+                                           float* __restrict__ resid, const RopeAppend& rp, int wm, int wn, int l16,
+                                           int lq) {
   constexpr bool GLU = (EPI == EPI_SWIGLU);
-  const int tid = threadIdx.x, lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int wm = wave >> 2, wn = wave & 3;
-  const int l16 = lane & 15, lq = lane >> 4;
-
-  // ---- workgroup id -> tile: the 32 workgroups resident on one XCD (ids congruent modulo 8)
-  // work on a 4 x 8 patch of neighbouring tiles and share operand panels through its L2
-  const int nt = tiles_m * tiles_n;
-  // chunks of 32 consecutive tiles go round-robin over the 8 XCDs; two-level order: groups of
-  // 16 tile rows; inside a group, columns of 8 tiles; inside a column, patches of 4 rows, row
-  // index fastest.  32 consecutive tiles are a 4 x 8 patch, 256 consecutive tiles (what the
-  // eight XCDs work on at the same time) a 16 x 16 block of the output.
-  const int slot = blockIdx.x >> 3;
-  const int l = ((slot >> 5) << 8) + ((blockIdx.x & 7) << 5) + (slot & 31);
-  if (l >= nt) return;
-  const TileAt ta = tile_at(l, tiles_m, tiles_n);
-  const int tm = ta.tm, tn = ta.tn;
-  const int m0 = tm * BM;
-  const int n0 = GLU ? tn * (BN / 2) : tn * BN;  // GLU: 128 output columns per tile
-
-  // ---- global -> LDS: wave w fills tile rows 32w..32w+31 of both operands, 8 rows per
-  // instruction; lane l supplies row 32w + 8i + l/8, physical chunk l%8.  Byte offsets from
-  // the operand's base (both operands are below 4 GB): the k-block's offset is added to the
-  // scalar base, so a fill costs no vector address arithmetic.
-  unsigned ao[FI], wo[FI];
-#pragma unroll
-  for (int i = 0; i < FI; ++i) {
-    const int row = wave * 32 + i * 8 + (lane >> 3);
-    const int c = (lane & 7) ^ ((row >> 1) & 7);
-    const int am = min(m0 + row, M - 1);
-    ao[i] = (unsigned)(((size_t)am * K + c * 8) * 2);
-    int wrow;
-    if constexpr (GLU) {
-      // tile row -> weight row: 32-row blocks alternate gate / up, so that a wave's 64 tile
-      // rows are the gate and the up projection of the same 32 output columns
-      const int blk = row >> 5;
-      const int f = min(n0 + (blk >> 1) * 32 + (row & 31), N - 1);
-      wrow = (blk & 1) * N + f;
-    } else {
-      wrow = min(n0 + row, N - 1);
-    }
-    wo[i] = (unsigned)(((size_t)wrow * K + c * 8) * 2);
-  }
-  const int fill_off = wave * 32 * ROWB;
-#define LS_FA(stage_, k0_, i_)                                                                        \
-  __builtin_amdgcn_global_load_lds((const void*)((const char*)A + (size_t)(k0_) * 2 + ao[i_]),        \
-      (lds_void*)(smem + (stage_) * STAGE_BYTES + fill_off + (i_) * 1024), 16, 0, 0);
-#define LS_FW(stage_, k0_, i_)                                                                        \
-  __builtin_amdgcn_global_load_lds((const void*)((const char*)W + (size_t)(k0_) * 2 + wo[i_]),        \
-      (lds_void*)(smem + (stage_) * STAGE_BYTES + TILE_BYTES + fill_off + (i_) * 1024), 16, 0, 0);
-  // both stages are free when a workgroup starts: stage 0 <- k-block 0 and stage 1 <- k-block 1
-  // at once (K >= 2 k-blocks); everything up to the first hand-over is set up while these
-  // first fills, which nothing else overlaps, are on their way
-#pragma unroll
-  for (int i = 0; i < FI; ++i) {
-    LS_FA(0, 0, i)
-    LS_FW(0, 0, i)
-  }
-#pragma unroll
-  for (int i = 0; i < FI; ++i) {
-    LS_FA(1, BK, i)
-    LS_FW(1, BK, i)
-  }
-
-  // ---- L2 prefetch.  A weight panel is shared by the 4 workgroups of a patch column, an
-  // activation panel by the 8 of a patch row; whoever asks first waits for HBM or the
-  // memory-side cache, and with two LDS stages a fill has one k-step to land.  So every
-  // workgroup touches its share of the patch's lines PF_AHEAD k-steps before they are filled:
-  // 64 of the 256 weight rows and 32 of the 256 activation rows, i.e. 8 + 4 lines per wavefront
-  // and k-step, fetched by one 4-byte LDS-direct load (its lanes share those 12 lines; the
-  // words go to a scratch piece of LDS nobody reads).  It is the youngest vector memory
-  // operation of the wavefront at every hand-over, which therefore waits for all but one
-  // (vmcnt(1)): vector memory loads return in order.  Measured at the 13B shape: the waits for
-  // fills at the hand-over (300-700 cycles per k-step without it) disappear, +4.4 %.
-  // The last k-steps of a tile prefetch the first k-blocks of tile l + 256 instead: the tile
-  // that the same XCD starts next in this slot, whichever of its CUs gets it, so that a new
-  // workgroup's first fills, which nothing overlaps, find their lines in L2.
-  auto pf_base = [&](const TileAt& t) -> const char* {
-    const int p = (lane & 15) < 12 ? (lane & 15) : (lane & 7);  // 12 distinct lines per wavefront
-    const int row_w = (t.full ? 64 * t.q4 : 0) + 8 * wave + (p & 7);
-    const int row_a = (t.full ? 32 * t.q8 : 0) + 4 * wave + (p & 3);
-    const int tn0 = GLU ? t.tn * (BN / 2) : t.tn * BN;
-    int wrow;
-    if constexpr (GLU) {
-      const int blk = row_w >> 5;
-      const int f = min(tn0 + (blk >> 1) * 32 + (row_w & 31), N - 1);
-      wrow = (blk & 1) * N + f;
-    } else {
-      wrow = min(tn0 + row_w, N - 1);
-    }
-    const int am = min(t.tm * BM + row_a, M - 1);
-    return (p < 8) ? (const char*)W + (size_t)wrow * K * 2 : (const char*)A + (size_t)am * K * 2;
-  };
-  const char* pf_ptr = pf_base(ta);
-  const char* pf_next = l + 256 < nt ? pf_base(tile_at(l + 256, tiles_m, tiles_n)) : pf_ptr;
-#define LS_PREFETCH(kb_)                                                                            \
-  __builtin_amdgcn_global_load_lds(                                                                 \
-      (const void*)((kb_) < KT ? pf_ptr + (size_t)(kb_) * (BK * 2)                                  \
-                               : pf_next + (size_t)min((kb_) - KT, KT - 1) * (BK * 2)),             \
-      (lds_void*)(smem + SMEM_BYTES), 4, 0, 0);
-  f32x4 acc[8][4];
-#pragma unroll
-  for (int i = 0; i < 8; ++i)
-#pragma unroll
-    for (int j = 0; j < 4; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-  // ---- LDS addresses of this lane's fragment reads in stage 0: fragment = 16 tile rows x 32 k,
-  // lane -> row lane%16, k-octet lane/16 (first half-step) or 4 + lane/16 (second); later row
-  // blocks are +2048 bytes (the swizzle term depends on row%16 only), stage 1 is +STAGE_BYTES
-  const unsigned lds0 = (unsigned)(size_t)(lds_void*)smem;
-  const unsigned xa0 = lds0 + swz(wm * 128 + l16, lq), xa1 = lds0 + swz(wm * 128 + l16, 4 + lq);
-  const unsigned wa0 = lds0 + TILE_BYTES + swz(wn * 64 + l16, lq);
-  const unsigned wa1 = lds0 + TILE_BYTES + swz(wn * 64 + l16, 4 + lq);
-  const int KT = K / BK;
-
-  bf16x8 xf[6], xe[2][2], wf[2][4];
-#define LS_SB() __builtin_amdgcn_sched_barrier(0);
-#define LS_RD(dst_, addr_, off_) \
-  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst_) : "v"(addr_), "n"(off_));
-  // wait until at most n_ of this wavefront's LDS reads are outstanding (other counters untouched)
-#define LS_WAITL(n_) __builtin_amdgcn_s_waitcnt(0xC07F | ((n_) << 8));
-  // activation fragment of row block i_ in half-step parity ws_: blocks 0..5 live in one set of
-  // registers, blocks 6 and 7 in two (see below)
-#define LS_X(ws_, i_) ((i_) < 6 ? xf[(i_) < 6 ? (i_) : 0] : xe[ws_][(i_) < 6 ? 0 : (i_) - 6])
-#define LS_MF(ws_, i_, j_) \
-  acc[i_][j_] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[ws_][j_], LS_X(ws_, i_), acc[i_][j_], 0, 0, 0);
-#define LS_NONE
-  // One row block of a half-step: four MFMAs; after the second the reads WR_ (the next
-  // half-step's weight fragment i_, row blocks 0..3 only), after the third an optional fill
-  // (F_), after the fourth the read XR_ (the row block's own activation fragment for the next
-  // half-step, row blocks 0..5).
-#define LS_BLOCK(ws_, i_, WR_, F_, XR_)                             \
-  LS_MF(ws_, i_, 0) LS_SB()                                         \
-  LS_MF(ws_, i_, 1) LS_SB()                                         \
-  WR_ LS_SB()                                                       \
-  LS_MF(ws_, i_, 2) LS_SB()                                         \
-  F_ LS_SB()                                                        \
-  LS_MF(ws_, i_, 3) LS_SB()                                         \
-  XR_ LS_SB()
-  // A half-step.  The fragments of row blocks 6 and 7 are double buffered and requested early
-  // (with the weight fragments of row blocks 2 and 3), so that the last read before the
-  // hand-over barrier is eight MFMAs old when the barrier waits for it.  Reads are issued in
-  // the order W0' X0' W1' X1' W2' X6' X2' W3' X7' X3' X4' X5' (primes: for the next half-step).
-  // Row block 0 needs X0 and all of W0..W3, i.e. the first eight reads of the previous
-  // half-step: four younger ones may be outstanding.  Row blocks 1 and 2 are covered by that
-  // wait.  Row block 3 needs X3, the tenth: two younger ones of the previous half-step plus the
-  // seven issued so far in this one.  Row block 4 needs the eleventh: one younger plus ten of
-  // this half-step; row block 5 the twelfth: none plus eleven.  Row blocks 6 and 7 need the
-  // sixth and the ninth, which the waits of row blocks 0 and 3 have covered.
-#define LS_HALF(ws_, xaddr_, waddr_, F0, F1, F2, F3, F4, F5, F6, F7)                                   \
-  LS_WAITL(4) LS_SB()                                                                                  \
-  LS_BLOCK(ws_, 0, LS_RD(wf[(ws_) ^ 1][0], waddr_, 0 * 2048), F0, LS_RD(xf[0], xaddr_, 0 * 2048))      \
-  LS_BLOCK(ws_, 1, LS_RD(wf[(ws_) ^ 1][1], waddr_, 1 * 2048), F1, LS_RD(xf[1], xaddr_, 1 * 2048))      \
-  LS_BLOCK(ws_, 2, LS_RD(wf[(ws_) ^ 1][2], waddr_, 2 * 2048) LS_RD(xe[(ws_) ^ 1][0], xaddr_, 6 * 2048), \
-           F2, LS_RD(xf[2], xaddr_, 2 * 2048))                                                         \
-  LS_WAITL(9) LS_SB()                                                                                  \
-  LS_BLOCK(ws_, 3, LS_RD(wf[(ws_) ^ 1][3], waddr_, 3 * 2048) LS_RD(xe[(ws_) ^ 1][1], xaddr_, 7 * 2048), \
-           F3, LS_RD(xf[3], xaddr_, 3 * 2048))                                                         \
-  LS_WAITL(11) LS_SB()                                                                                 \
-  LS_BLOCK(ws_, 4, LS_NONE, F4, LS_RD(xf[4], xaddr_, 4 * 2048))                                        \
-  LS_WAITL(11) LS_SB()                                                                                 \
-  LS_BLOCK(ws_, 5, LS_NONE, F5, LS_RD(xf[5], xaddr_, 5 * 2048))                                        \
-  LS_BLOCK(ws_, 6, LS_NONE, F6, LS_NONE)                                                               \
-  LS_BLOCK(ws_, 7, LS_NONE, F7, LS_NONE)
-  // own LDS reads done, own fills landed, then everyone
-#define LS_HANDOVER(imm_)                    \
-  asm volatile("" ::: "memory");             \
-  __builtin_amdgcn_s_waitcnt(imm_);          \
-  __builtin_amdgcn_sched_barrier(0);         \
-  __builtin_amdgcn_s_barrier();              \
-  __builtin_amdgcn_sched_barrier(0);         \
-  asm volatile("" ::: "memory");
-
-  // ---- prologue: prefetch, hand over stage 0 (the eight fills of stage 1 and the prefetch may
-  // still be in flight: vmcnt(9)), first fragments
-  LS_PREFETCH(1 + PF_AHEAD)
-  LS_HANDOVER(0x0079)
-  LS_SB()
-  LS_RD(wf[0][0], wa0, 0 * 2048) LS_RD(xf[0], xa0, 0 * 2048)
-  LS_RD(wf[0][1], wa0, 1 * 2048) LS_RD(xf[1], xa0, 1 * 2048)
-  LS_RD(wf[0][2], wa0, 2 * 2048) LS_RD(xe[0][0], xa0, 6 * 2048) LS_RD(xf[2], xa0, 2 * 2048)
-  LS_RD(wf[0][3], wa0, 3 * 2048) LS_RD(xe[0][1], xa0, 7 * 2048) LS_RD(xf[3], xa0, 3 * 2048)
-  LS_RD(xf[4], xa0, 4 * 2048) LS_RD(xf[5], xa0, 5 * 2048)
-  LS_SB()
-
-  for (int kt = 0; kt < KT; ++kt) {
-    const int buf = kt & 1;
-    const unsigned sx = (unsigned)buf * STAGE_BYTES, so = (unsigned)(buf ^ 1) * STAGE_BYTES;
-    // first half-step: computes k-octets 0..3 of stage buf, requests octets 4..7 of the same stage
-    {
-      const unsigned xa = xa1 + sx, wa = wa1 + sx;
-      LS_SB()
-      LS_HALF(0, xa, wa, LS_NONE, LS_NONE, LS_NONE, LS_NONE, LS_NONE, LS_NONE, LS_NONE, LS_NONE)
-    }
-    LS_HANDOVER(0x0071)  // vmcnt(1): all fills, not the youngest prefetch
-    // second half-step: computes octets 4..7, requests octets 0..3 of the other stage (the last
-    // k-step requests fragments nobody uses; they are drained below) and refills stage buf
-    {
-      const unsigned xa = xa0 + so, wa = wa0 + so;
-      // the last two k-steps have nothing left to fetch: they fill the retired stage once more
-      // with the last k-block (lines that are in L2 anyway) instead of branching around every fill
-      const int k2 = min(kt + 2, KT - 1) * BK;
-      LS_SB()
-      LS_HALF(1, xa, wa, LS_FA(buf, k2, 0), LS_FW(buf, k2, 0), LS_FA(buf, k2, 1), LS_FW(buf, k2, 1), LS_FA(buf, k2, 2),
-              LS_FW(buf, k2, 2), LS_FA(buf, k2, 3), LS_FW(buf, k2, 3) LS_PREFETCH(kt + 2 + PF_AHEAD))
-    }
-  }
-  // the reads requested by the last half-step land in registers the epilogue may reuse, and no
-  // LDS-direct load may still be on its way when the workgroup gives up its LDS
-  LS_SB()
-  __builtin_amdgcn_s_waitcnt(0x0070);
-  LS_SB()
-#undef LS_FA
-#undef LS_FW
-#undef LS_SB
-#undef LS_RD
-#undef LS_WAITL
-#undef LS_MF
-#undef LS_X
-#undef LS_NONE
-#undef LS_BLOCK
-#undef LS_HALF
-#undef LS_HANDOVER
-#undef LS_PREFETCH
-
-  // ---- epilogue: acc[i][j][r] is C[m0 + 128 wm + 16 i + lane%16][n0 + 64 wn + 16 j + 4 (lane/16) + r]
   const bool vec = (N & 3) == 0;
   if constexpr (EPI == EPI_ROPE) {
     // A wavefront's 64 columns lie inside one head (head_dim 64 or 128): query, key or value.
@@ -376,46 +166,51 @@ k_gemm_mfma(const bf16* __restrict__ A, const bf16* __restrict__ W, int M, int N
     const int head = ncol0 / rp.hd, dd0 = ncol0 - head * rp.hd;
     const bool is_q = head < rp.hq, is_v = head >= rp.hq + rp.hkv;
     const int kh = is_v ? head - rp.hq - rp.hkv : head - rp.hq;
+    bf16* const cache = rp.kc + (is_v ? rp.vc - rp.kc : (ptrdiff_t)0);  // (a plain choice between the two pointers is compiled into a table in private memory)
     int pos[8], seq[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-      const int m = m0 + wm * 128 + i * 16 + l16;
-      pos[i] = m < M ? rp.row_pos[m] : -1;
-      seq[i] = (m < M && !is_q) ? rp.row_seq[m] : 0;
+      // (no load here is conditional, and none is left unused on any path: a load that the
+      // compiler cannot prove finished would make it wait for ALL vector memory operations,
+      // fills included, inside the k-loop that follows this epilogue in the next tile)
+      const int m = m0 + wm * 128 + i * 16 + l16, mm = min(m, M - 1);
+      const int p = rp.row_pos[mm], sq = rp.row_seq[mm];
+      pos[i] = m < M ? p : -1;
+      seq[i] = sq;
     }
+    // Straight-line code from here to the stores: table loads are made for value heads too and
+    // the choice between a turned and an untouched value is a bit select, so that the compiler
+    // has no branch to build around a load.
     f32x4 tab[2][4];
 #define LS_TAB_LOAD(i_, set_)                                                                         \
-  if (!is_v) {                                                                                        \
-    _Pragma("unroll") for (int j = 0; j < 4; ++j)                                                     \
-      tab[set_][j] = *reinterpret_cast<const f32x4*>(                                                 \
-          rp.cs + ((size_t)max(pos[i_], 0) * (rp.hd >> 1) + ((dd0 + j * 16 + 4 * lq) >> 1)) * 2);     \
-  }
+  _Pragma("unroll") for (int j = 0; j < 4; ++j)                                                       \
+    tab[set_][j] = *reinterpret_cast<const f32x4*>(                                                   \
+        rp.cs + ((size_t)max(pos[i_], 0) * (rp.hd >> 1) + ((dd0 + j * 16 + 4 * lq) >> 1)) * 2);
     LS_TAB_LOAD(0, 0)
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-      if (i + 1 < 8) LS_TAB_LOAD(i + 1, (i + 1) & 1)
+      if (i + 1 < 8) { LS_TAB_LOAD(i + 1, (i + 1) & 1) }
       const int m = m0 + wm * 128 + i * 16 + l16;
       // a row past the end of the call stores nothing; a row whose sequence has no room left
       // keeps its query as projected and appends nothing, as with the separate rotation kernel
       const bool live = m < M && (pos[i] >= 0 || is_q);
-      const bool turn = !is_v && pos[i] >= 0;
+      const unsigned turn = (!is_v && pos[i] >= 0) ? 0xFFFFFFFFu : 0u;
       bf16x4 y[4];
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
-        f32x4 v = acc[i][j];
-        if (turn) {
-          const f32x4 t = tab[i & 1][j];  // cos, sin of pair dd/2; cos, sin of pair dd/2 + 1
-          // the projection's output is rounded to bf16 first, as the separate rotation kernel sees it
-          const float u0 = (float)(bf16)v[0], u1 = (float)(bf16)v[1], u2 = (float)(bf16)v[2], u3 = (float)(bf16)v[3];
-          v[0] = u0 * t[0] - u1 * t[1];
-          v[1] = u0 * t[1] + u1 * t[0];
-          v[2] = u2 * t[2] - u3 * t[3];
-          v[3] = u2 * t[3] + u3 * t[2];
-        }
-        y[j] = to_bf16x4(v);
+        const f32x4 v = acc[i][j];
+        const f32x4 t = tab[i & 1][j];  // cos, sin of pair dd/2; cos, sin of pair dd/2 + 1
+        // the projection's output is rounded to bf16 first, as the separate rotation kernel sees it
+        const float u0 = (float)(bf16)v[0], u1 = (float)(bf16)v[1], u2 = (float)(bf16)v[2], u3 = (float)(bf16)v[3];
+        f32x4 w;
+        w[0] = pick_bits(turn, u0 * t[0] - u1 * t[1], v[0]);
+        w[1] = pick_bits(turn, u0 * t[1] + u1 * t[0], v[1]);
+        w[2] = pick_bits(turn, u2 * t[2] - u3 * t[3], v[2]);
+        w[3] = pick_bits(turn, u2 * t[3] + u3 * t[2], v[3]);
+        y[j] = to_bf16x4(w);
       }
       bf16* row = is_q ? (bf16*)outv + (size_t)m * N + ncol0
-                       : (is_v ? rp.vc : rp.kc) + (((size_t)seq[i] * rp.hkv + kh) * rp.max_seq + max(pos[i], 0)) * rp.hd + dd0;
+                       : cache + (((size_t)seq[i] * rp.hkv + kh) * rp.max_seq + max(pos[i], 0)) * rp.hd + dd0;
 #pragma unroll
       for (int jp = 0; jp < 2; ++jp) {
         const u32x4 o = side_by_side(y[2 * jp], y[2 * jp + 1]);  // every lane takes part
@@ -537,6 +332,288 @@ k_gemm_mfma(const bf16* __restrict__ A, const bf16* __restrict__ W, int M, int N
 }
 
 template <int EPI>
+__global__ void __launch_bounds__(NWAVE * 64, 1)
+k_gemm_mfma(const bf16* __restrict__ A, const bf16* __restrict__ W, int M, int N, int K,
+            void* __restrict__ outv, float* __restrict__ resid, int tiles_m, int tiles_n, RopeAppend rp) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  typedef __attribute__((address_space(3))) void lds_void;
+  constexpr bool GLU = (EPI == EPI_SWIGLU);
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave >> 2, wn = wave & 3;
+  const int l16 = lane & 15, lq = lane >> 4;
+
+  // ---- workgroup id -> tiles.  256 workgroups, one per CU (a workgroup's LDS fills a CU), each
+  // walking tiles l, l + 256, l + 512, ...  Workgroup ids congruent modulo 8 land on the same
+  // XCD, and its 32 workgroups take 32 consecutive tiles at a time.  Tile order, two levels:
+  // groups of 16 tile rows; inside a group, columns of 8 tiles; inside a column, patches of 4
+  // rows, row index fastest.  32 consecutive tiles are a 4 x 8 patch whose operand panels the
+  // XCD's L2 shares, 256 consecutive tiles (what the eight XCDs work on at the same time) a
+  // 16 x 16 block of the output.
+  const int nt = tiles_m * tiles_n;
+  int l = ((blockIdx.x & 7) << 5) + (blockIdx.x >> 3);
+  if (l >= nt) return;
+  TileAt ta = tile_at(l, tiles_m, tiles_n);
+  bool has_next = l + PERSISTENT_WGS < nt;
+  TileAt tb = tile_at(has_next ? l + PERSISTENT_WGS : l, tiles_m, tiles_n);  // the tile after this one
+  int m0 = ta.tm * BM;
+  int n0 = GLU ? ta.tn * (BN / 2) : ta.tn * BN;  // GLU: 128 output columns per tile
+
+  // ---- global -> LDS: wave w fills tile rows 32w..32w+31 of both operands, 8 rows per
+  // instruction; lane l supplies row 32w + 8i + l/8, physical chunk l%8.  Byte offsets from
+  // the operand's base (both operands are below 4 GB): the k-block's offset is added to the
+  // scalar base, so a fill costs no vector address arithmetic.
+  unsigned ao[FI], wo[FI];
+  auto fill_offsets = [&](const TileAt& t) {
+    const int tm0 = t.tm * BM, tn0 = GLU ? t.tn * (BN / 2) : t.tn * BN;
+#pragma unroll
+    for (int i = 0; i < FI; ++i) {
+      const int row = wave * 32 + i * 8 + (lane >> 3);
+      const int c = (lane & 7) ^ ((row >> 1) & 7);
+      const int am = min(tm0 + row, M - 1);
+      ao[i] = (unsigned)(((size_t)am * K + c * 8) * 2);
+      int wrow;
+      if constexpr (GLU) {
+        // tile row -> weight row: 32-row blocks alternate gate / up, so that a wave's 64 tile
+        // rows are the gate and the up projection of the same 32 output columns
+        const int blk = row >> 5;
+        const int f = min(tn0 + (blk >> 1) * 32 + (row & 31), N - 1);
+        wrow = (blk & 1) * N + f;
+      } else {
+        wrow = min(tn0 + row, N - 1);
+      }
+      wo[i] = (unsigned)(((size_t)wrow * K + c * 8) * 2);
+    }
+  };
+  fill_offsets(ta);
+  const int fill_off = wave * 32 * ROWB;
+#define LS_FA(stage_, k0_, i_)                                                                        \
+  __builtin_amdgcn_global_load_lds((const void*)((const char*)A + (size_t)(k0_) * 2 + ao[i_]),        \
+      (lds_void*)(smem + (stage_) * STAGE_BYTES + fill_off + (i_) * 1024), 16, 0, 0);
+#define LS_FW(stage_, k0_, i_)                                                                        \
+  __builtin_amdgcn_global_load_lds((const void*)((const char*)W + (size_t)(k0_) * 2 + wo[i_]),        \
+      (lds_void*)(smem + (stage_) * STAGE_BYTES + TILE_BYTES + fill_off + (i_) * 1024), 16, 0, 0);
+  // both stages are free when a workgroup starts: stage 0 <- k-block 0 and stage 1 <- k-block 1
+  // of its first tile at once (K >= 2 k-blocks); everything up to the first hand-over is set
+  // up while these fills are on their way
+#pragma unroll
+  for (int i = 0; i < FI; ++i) {
+    LS_FA(0, 0, i)
+    LS_FW(0, 0, i)
+  }
+#pragma unroll
+  for (int i = 0; i < FI; ++i) {
+    LS_FA(1, BK, i)
+    LS_FW(1, BK, i)
+  }
+
+  // ---- L2 prefetch.  A weight panel is shared by the 4 workgroups of a patch column, an
+  // activation panel by the 8 of a patch row; whoever asks first waits for HBM or the
+  // memory-side cache, and with two LDS stages a fill has one k-step to land.  So every
+  // workgroup touches its share of the patch's lines PF_AHEAD k-steps before they are filled:
+  // 64 of the 256 weight rows and 32 of the 256 activation rows, i.e. 8 + 4 lines per wavefront
+  // and k-step, fetched by one 4-byte LDS-direct load (its lanes share those 12 lines; the
+  // words go to a scratch piece of LDS nobody reads).  It is the youngest vector memory
+  // operation of the wavefront at every hand-over, which therefore waits for all but one
+  // (vmcnt(1)): vector memory loads return in order.  Measured at the 13B shape: the waits for
+  // fills at the hand-over (300-700 cycles per k-step without it) disappear, +4.4 %.
+  // The last k-steps of a tile prefetch the first k-blocks of the workgroup's next tile.
+  auto pf_base = [&](const TileAt& t) -> const char* {
+    const int p = (lane & 15) < 12 ? (lane & 15) : (lane & 7);  // 12 distinct lines per wavefront
+    const int row_w = (t.full ? 64 * t.q4 : 0) + 8 * wave + (p & 7);
+    const int row_a = (t.full ? 32 * t.q8 : 0) + 4 * wave + (p & 3);
+    const int tn0 = GLU ? t.tn * (BN / 2) : t.tn * BN;
+    int wrow;
+    if constexpr (GLU) {
+      const int blk = row_w >> 5;
+      const int f = min(tn0 + (blk >> 1) * 32 + (row_w & 31), N - 1);
+      wrow = (blk & 1) * N + f;
+    } else {
+      wrow = min(tn0 + row_w, N - 1);
+    }
+    const int am = min(t.tm * BM + row_a, M - 1);
+    return (p < 8) ? (const char*)W + (size_t)wrow * K * 2 : (const char*)A + (size_t)am * K * 2;
+  };
+  const char* pf_ptr = pf_base(ta);
+  const char* pf_next = has_next ? pf_base(tb) : pf_ptr;
+#define LS_PREFETCH(kb_)                                                                            \
+  __builtin_amdgcn_global_load_lds(                                                                 \
+      (const void*)((kb_) < KT ? pf_ptr + (size_t)(kb_) * (BK * 2)                                  \
+                               : pf_next + (size_t)min((kb_) - KT, KT - 1) * (BK * 2)),             \
+      (lds_void*)(smem + SMEM_BYTES), 4, 0, 0);
+  f32x4 acc[8][4];
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  // ---- LDS addresses of this lane's fragment reads in stage 0: fragment = 16 tile rows x 32 k,
+  // lane -> row lane%16, k-octet lane/16 (first half-step) or 4 + lane/16 (second); later row
+  // blocks are +2048 bytes (the swizzle term depends on row%16 only), stage 1 is +STAGE_BYTES
+  const unsigned lds0 = (unsigned)(size_t)(lds_void*)smem;
+  const unsigned xa0 = lds0 + swz(wm * 128 + l16, lq), xa1 = lds0 + swz(wm * 128 + l16, 4 + lq);
+  const unsigned wa0 = lds0 + TILE_BYTES + swz(wn * 64 + l16, lq);
+  const unsigned wa1 = lds0 + TILE_BYTES + swz(wn * 64 + l16, 4 + lq);
+  const int KT = K / BK;
+
+  bf16x8 xf[6], xe[2][2], wf[2][4];
+#define LS_SB() __builtin_amdgcn_sched_barrier(0);
+#define LS_RD(dst_, addr_, off_) \
+  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst_) : "v"(addr_), "n"(off_));
+  // wait until at most n_ of this wavefront's LDS reads are outstanding (other counters untouched)
+#define LS_WAITL(n_) __builtin_amdgcn_s_waitcnt(0xC07F | ((n_) << 8));
+  // activation fragment of row block i_ in half-step parity ws_: blocks 0..5 live in one set of
+  // registers, blocks 6 and 7 in two (see below)
+#define LS_X(ws_, i_) ((i_) < 6 ? xf[(i_) < 6 ? (i_) : 0] : xe[ws_][(i_) < 6 ? 0 : (i_) - 6])
+#define LS_MF(ws_, i_, j_) \
+  acc[i_][j_] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[ws_][j_], LS_X(ws_, i_), acc[i_][j_], 0, 0, 0);
+#define LS_NONE
+  // One row block of a half-step: four MFMAs; after the second the reads WR_ (the next
+  // half-step's weight fragment i_, row blocks 0..3 only), after the third an optional fill
+  // (F_), after the fourth the read XR_ (the row block's own activation fragment for the next
+  // half-step, row blocks 0..5).
+#define LS_BLOCK(ws_, i_, WR_, F_, XR_)                             \
+  LS_MF(ws_, i_, 0) LS_SB()                                         \
+  LS_MF(ws_, i_, 1) LS_SB()                                         \
+  WR_ LS_SB()                                                       \
+  LS_MF(ws_, i_, 2) LS_SB()                                         \
+  F_ LS_SB()                                                        \
+  LS_MF(ws_, i_, 3) LS_SB()                                         \
+  XR_ LS_SB()
+  // A half-step.  The fragments of row blocks 6 and 7 are double buffered and requested early
+  // (with the weight fragments of row blocks 2 and 3), so that the last read before the
+  // hand-over barrier is eight MFMAs old when the barrier waits for it.  Reads are issued in
+  // the order W0' X0' W1' X1' W2' X6' X2' W3' X7' X3' X4' X5' (primes: for the next half-step).
+  // Row block 0 needs X0 and all of W0..W3, i.e. the first eight reads of the previous
+  // half-step: four younger ones may be outstanding.  Row blocks 1 and 2 are covered by that
+  // wait.  Row block 3 needs X3, the tenth: two younger ones of the previous half-step plus the
+  // seven issued so far in this one.  Row block 4 needs the eleventh: one younger plus ten of
+  // this half-step; row block 5 the twelfth: none plus eleven.  Row blocks 6 and 7 need the
+  // sixth and the ninth, which the waits of row blocks 0 and 3 have covered.
+#define LS_HALF(ws_, xaddr_, waddr_, F0, F1, F2, F3, F4, F5, F6, F7)                                   \
+  LS_WAITL(4) LS_SB()                                                                                  \
+  LS_BLOCK(ws_, 0, LS_RD(wf[(ws_) ^ 1][0], waddr_, 0 * 2048), F0, LS_RD(xf[0], xaddr_, 0 * 2048))      \
+  LS_BLOCK(ws_, 1, LS_RD(wf[(ws_) ^ 1][1], waddr_, 1 * 2048), F1, LS_RD(xf[1], xaddr_, 1 * 2048))      \
+  LS_BLOCK(ws_, 2, LS_RD(wf[(ws_) ^ 1][2], waddr_, 2 * 2048) LS_RD(xe[(ws_) ^ 1][0], xaddr_, 6 * 2048), \
+           F2, LS_RD(xf[2], xaddr_, 2 * 2048))                                                         \
+  LS_WAITL(9) LS_SB()                                                                                  \
+  LS_BLOCK(ws_, 3, LS_RD(wf[(ws_) ^ 1][3], waddr_, 3 * 2048) LS_RD(xe[(ws_) ^ 1][1], xaddr_, 7 * 2048), \
+           F3, LS_RD(xf[3], xaddr_, 3 * 2048))                                                         \
+  LS_WAITL(11) LS_SB()                                                                                 \
+  LS_BLOCK(ws_, 4, LS_NONE, F4, LS_RD(xf[4], xaddr_, 4 * 2048))                                        \
+  LS_WAITL(11) LS_SB()                                                                                 \
+  LS_BLOCK(ws_, 5, LS_NONE, F5, LS_RD(xf[5], xaddr_, 5 * 2048))                                        \
+  LS_BLOCK(ws_, 6, LS_NONE, F6, LS_NONE)                                                               \
+  LS_BLOCK(ws_, 7, LS_NONE, F7, LS_NONE)
+  // own LDS reads done, own fills landed, then everyone
+#define LS_HANDOVER(imm_)                    \
+  asm volatile("" ::: "memory");             \
+  __builtin_amdgcn_s_waitcnt(imm_);          \
+  __builtin_amdgcn_sched_barrier(0);         \
+  __builtin_amdgcn_s_barrier();              \
+  __builtin_amdgcn_sched_barrier(0);         \
+  asm volatile("" ::: "memory");
+
+  // first fragments of a tile: k-octets 0..3 of the stage at byte offset so_
+#define LS_FIRST_READS(so_)                                                                            \
+  LS_SB()                                                                                              \
+  LS_RD(wf[0][0], wa0 + (so_), 0 * 2048) LS_RD(xf[0], xa0 + (so_), 0 * 2048)                           \
+  LS_RD(wf[0][1], wa0 + (so_), 1 * 2048) LS_RD(xf[1], xa0 + (so_), 1 * 2048)                           \
+  LS_RD(wf[0][2], wa0 + (so_), 2 * 2048) LS_RD(xe[0][0], xa0 + (so_), 6 * 2048) LS_RD(xf[2], xa0 + (so_), 2 * 2048) \
+  LS_RD(wf[0][3], wa0 + (so_), 3 * 2048) LS_RD(xe[0][1], xa0 + (so_), 7 * 2048) LS_RD(xf[3], xa0 + (so_), 3 * 2048) \
+  LS_RD(xf[4], xa0 + (so_), 4 * 2048) LS_RD(xf[5], xa0 + (so_), 5 * 2048)                              \
+  LS_SB()
+
+  // ---- prologue: prefetch, hand over stage 0 (the eight fills of stage 1 and the prefetch may
+  // still be in flight: vmcnt(9)), first fragments
+  LS_PREFETCH(1 + PF_AHEAD)
+  LS_HANDOVER(0x0079)
+  LS_FIRST_READS(0u)
+
+  // The workgroup's k-steps form one stream across its tiles: stage = (k-steps so far) & 1, and
+  // the fills of a tile's last two k-steps already fetch the first two k-blocks of the
+  // workgroup's next tile, so that its epilogue, not an idle CU, covers their latency.
+  int kf = 2;       // next k-block to fetch, of the tile that ao/wo point at
+  unsigned gk = 0;  // k-steps done
+  for (;;) {
+    for (int kt = 0; kt < KT; ++kt, ++gk) {
+      const int buf = gk & 1;
+      const unsigned sx = (unsigned)buf * STAGE_BYTES, so = (unsigned)(buf ^ 1) * STAGE_BYTES;
+      // first half-step: computes k-octets 0..3 of stage buf, requests octets 4..7 of the same stage
+      {
+        const unsigned xa = xa1 + sx, wa = wa1 + sx;
+        LS_SB()
+        LS_HALF(0, xa, wa, LS_NONE, LS_NONE, LS_NONE, LS_NONE, LS_NONE, LS_NONE, LS_NONE, LS_NONE)
+      }
+      // vmcnt(1): all fills, not the youngest prefetch.  (Right after an epilogue this also waits
+      // for all but the last of its stores; a hand-over that lets them pass, with the fills
+      // waited for before the epilogue instead, measured 1-2 % slower in the residual GEMMs.)
+      LS_HANDOVER(0x0071)
+      // second half-step: computes octets 4..7, requests octets 0..3 of the other stage and
+      // refills stage buf
+      {
+        if (kf == KT) {
+          // nothing left to fetch for this tile: go on with the next one's first k-blocks; the
+          // very last tile fills the retired stage once more with its last k-block (lines that
+          // are in L2 anyway) instead of branching around every fill
+          if (has_next) {
+            fill_offsets(tb);
+            kf = 0;
+          } else {
+            kf = KT - 1;
+          }
+        }
+        const unsigned xa = xa0 + so, wa = wa0 + so;
+        const int k2 = kf * BK;
+        ++kf;
+        LS_SB()
+        LS_HALF(1, xa, wa, LS_FA(buf, k2, 0), LS_FW(buf, k2, 0), LS_FA(buf, k2, 1), LS_FW(buf, k2, 1), LS_FA(buf, k2, 2),
+                LS_FW(buf, k2, 2), LS_FA(buf, k2, 3), LS_FW(buf, k2, 3) LS_PREFETCH(kt + 2 + PF_AHEAD))
+      }
+    }
+    // the fragments requested by the last half-step land in registers the epilogue may reuse:
+    // wait for them (LDS reads only; fills stay in flight), and request them again afterwards
+    LS_SB()
+    LS_WAITL(0)
+    LS_SB()
+    store_tile<EPI>(acc, m0, n0, M, N, outv, resid, rp, wm, wn, l16, lq);
+    if (!has_next) break;
+    l += PERSISTENT_WGS;
+    ta = tb;
+    has_next = l + PERSISTENT_WGS < nt;
+    tb = tile_at(has_next ? l + PERSISTENT_WGS : l, tiles_m, tiles_n);
+    m0 = ta.tm * BM;
+    n0 = GLU ? ta.tn * (BN / 2) : ta.tn * BN;
+    pf_ptr = pf_next;
+    pf_next = has_next ? pf_base(tb) : pf_ptr;
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+    // the new tile's first k-block landed before the hand-over of the last k-step
+    LS_FIRST_READS((unsigned)(gk & 1) * STAGE_BYTES)
+  }
+  // no LDS-direct load may still be on its way when the workgroup gives up its LDS
+  LS_SB()
+  __builtin_amdgcn_s_waitcnt(0x0070);
+  LS_SB()
+#undef LS_FIRST_READS
+#undef LS_FA
+#undef LS_FW
+#undef LS_SB
+#undef LS_RD
+#undef LS_WAITL
+#undef LS_MF
+#undef LS_X
+#undef LS_NONE
+#undef LS_BLOCK
+#undef LS_HALF
+#undef LS_HANDOVER
+#undef LS_PREFETCH
+
+}
+
+template <int EPI>
 void launch_t(const void* A, const void* W, int M, int N, int K, void* out, float* resid, hipStream_t st,
               const RopeAppend& rope = RopeAppend{}) {
   static std::atomic<uint64_t> lds_allowed{0};
@@ -546,7 +623,8 @@ void launch_t(const void* A, const void* W, int M, int N, int K, void* out, floa
   const int ncols = (EPI == EPI_SWIGLU) ? BN / 2 : BN;
   const int tiles_n = (N + ncols - 1) / ncols;
   const int nt = tiles_m * tiles_n;
-  const int grid = ((nt + 255) / 256) * 256;
+  (void)nt;
+  const int grid = PERSISTENT_WGS;  // workgroups whose first tile does not exist leave at once
   launch_kernel(k_gemm_mfma<EPI>, dim3(grid), dim3(NWAVE * 64), LDS_BYTES, st, (const bf16*)A, (const bf16*)W, M, N,
                 K, out, resid, tiles_m, tiles_n, rope);
 }

@@ -132,6 +132,28 @@ def test_prompt_gemm_edges_rows_and_columns_that_fill_no_whole_tile_or_vector():
         gpu.close()
 
 
+def test_prompt_gemm_workgroups_that_walk_several_tiles():
+    """The prompt GEMM runs 256 workgroups that each walk tiles l, l + 256, ... as one stream of
+    k-steps, the fills of a tile's last two k-steps already fetching the next tile: prompt
+    passes whose gate-up GEMM has more than 256 tiles, with ragged last tile rows and columns,
+    with an odd number of k-steps per tile (the LDS stage a tile starts in then alternates
+    from tile to tile) and an even one."""
+    for ffn, d, lengths in ((1412, 320, [2047, 2300, 2654, 2000]), (1800, 256, [3000, 2999, 1300])):
+        shape = synth.StageShape("bf16", 2, d, d // 64, d // 64, 64, ffn, 0)
+        seed = 67
+        B, S = len(lengths), max(lengths)
+        T = sum(lengths)
+        assert ((T + 255) // 256) * ((ffn + 127) // 128) > 256 and T % 256 and ffn % 128
+        gpu = make_gpu(shape, seed, 0, 2, B, S + 2, T)
+        ora = make_oracle(shape, seed, 0, 2, B, S + 2)
+        x = synth.hidden_states(shape, seed + 1, T)
+        tag = "d%d F%d T%d" % (d, ffn, T)
+        check_close(to_host(gpu.prefill(to_dev(shape, x), lengths)), ora.prefill(x, lengths), "bf16", tag + " prompt")
+        xs = synth.hidden_states(shape, seed + 2, B)
+        check_close(to_host(gpu.decode(to_dev(shape, xs), B, S)), ora.decode(xs), "bf16", tag + " step")
+        gpu.close()
+
+
 def test_split_stages_equal_whole_stage():
     """Running layers [0,k) then [k,L) as two stages equals one stage [0,L)."""
     shape, seed, lengths = MINI_BF16.with_(vocab=0), 5, [33, 8]
