@@ -5,13 +5,12 @@
 // A register-only loop of v_mfma_f32_32x32x16_bf16 with varied operands settles at about
 // 1.8 GHz (1.82 PFLOP/s), the same loop of v_mfma_f32_16x16x32_bf16 at 2.15 GHz
 // (2.2 PFLOP/s), both at 2.4 GHz with all-zero operands: per multiply-add the 16x16x32 form
-// moves half the fp32 accumulator bytes through the register file.  A first version of this
-// kernel on the 32x32x16 form ran its k-loop at 1.75 GHz, this one runs at 2.0 GHz.
+// moves half the fp32 accumulator bytes through the register file.
 //
-// Tile and data path: one 512-thread workgroup (8 wavefronts, 2 x 4) owns a 256 x 256 tile of
-// C and walks K in steps of 64.  Both operands are K-contiguous, so a lane's 16-byte global
-// load is exactly the 8-element K slice an MFMA operand wants.  Tiles go from global memory
-// straight into LDS (global_load_lds_dwordx4: no staging registers, no LDS store
+// Tile and data path: one 256-thread workgroup (4 wavefronts, 2 x 2, one per SIMD) owns a
+// 256 x 256 tile of C and walks K in steps of 64.  Both operands are K-contiguous, so a lane's
+// 16-byte global load is exactly the 8-element K slice an MFMA operand wants.  Tiles go from
+// global memory straight into LDS (global_load_lds_dwordx4: no staging registers, no LDS store
 // instructions) into a ring of two stages of 64 KB (LDS has no room for a third at this tile
 // size, and rings of narrower k-steps measured slower: 64-byte row pieces cost twice the
 // requests of whole 128-byte lines).  One such instruction fills 1 KB = 8 tile rows of 128
@@ -19,49 +18,60 @@
 // of row r fetches logical chunk p ^ ((r/2)&7) -- so that the 16 rows a quarter-wave reads for
 // an MFMA operand fall into different banks (LDS has 64 banks here).
 //
-// A wavefront owns 128 rows x 64 columns of C = 8 x 4 MFMA tiles of 16 x 16.  The weight
+// A wavefront owns 128 rows x 128 columns of C = 8 x 8 MFMA tiles of 16 x 16; the 256
+// accumulator registers live in the AGPR half of a wavefront's 512 registers, the operand
+// fragments of a half-step (8 + 8 of 4 registers) in two sets in the VGPR half.  The weight
 // fragment is the instruction's A operand and the activation fragment its B operand, so in
 // the result a lane holds row m = lane%16 of the tile and FOUR CONSECUTIVE columns
-// n = 4*(lane/16) .. +3: the epilogues store 8 or 16 bytes per lane.
+// n = 4*(lane/16) .. +3.
 //
-// The k-loop is written out in issue order.  A k-step is two half-steps of 32 MFMAs (k = 32
-// each).  Within a half-step the activation fragments of row blocks 0..5 live in ONE set of
-// registers: the fragment of row block i is used by four consecutive MFMAs and reloaded for
-// the next half-step right after the last of them, 28 MFMAs before it is needed again; the
-// four weight fragments and the activation fragments of row blocks 6 and 7 are double
-// buffered.  The LDS reads are inline assembly and the waits for them are explicit
+// Why four wavefronts of 128 x 128 and not eight of 128 x 64 (the previous version of this
+// kernel, two per SIMD): shader-clock stamps around the hand-over showed that of the two
+// wavefronts of a SIMD the older one is served first by the matrix pipe: it finished its 64
+// MFMAs of a k-step (1024 cycles of matrix work) after 1480 cycles and then waited 1160 cycles
+// at the barrier, while the younger one needed 2460 -- alone on the SIMD for the last third,
+// where a single instruction stream with its own waits kept the pipe only two thirds busy.
+// One wavefront per SIMD has nobody to wait for (all four arrive within 20 cycles of each
+// other), reads a third fewer operand bytes from LDS per multiply-add, and its k-loop took
+// 109.5 us per 256 x 256 x 5120 tile against 114.5; what it loses is the second wavefront that
+// covered the issue slots of the fill instructions (about 12 cycles of an idle matrix pipe per
+// global_load_lds, 200 of a k-step's 2740 cycles; a k-step's 128 MFMAs need 2048) and half of
+// the memory-level parallelism in the epilogues.
+//
+// The k-loop is written out in issue order.  A k-step is two half-steps of 64 MFMAs (k = 32
+// each).  The LDS reads are inline assembly and the waits for them are explicit
 // s_waitcnt lgkmcnt(n) with the exact number of younger reads that may still be in flight:
 // the compiler, which treats an LDS-direct load as a possible writer of anything in LDS, waits
 // for ALL outstanding LDS reads before every dependent MFMA once such a load is in the
-// function.  LDS reads return in order; the counts are derived next to the macro that issues
-// them.
+// function.  LDS reads return in order; the counts are derived next to the macros.
+// The same compiler pass decides where the k-loop waits for vector memory: a register that it
+// cannot prove free of a pending load when the loop is entered again after an epilogue (a
+// spilled value reloaded on one path, a load whose result one branch does not use) makes it
+// put s_waitcnt vmcnt(0) in front of an MFMA INSIDE the k-loop, which then waits for every
+// fill as soon as it is issued (20 % of a launch, seen twice).  Hence the straight-line
+// epilogues, the lane numbers that pass through empty asm statements (so that what is derived
+// from them is computed where it is used and nothing is spilled across the loop), and the
+// scheduling barriers between the row blocks of an epilogue.
 //
 // Stage hand-over: the barrier sits between the two half-steps of a k-step.  Before it a
 // wavefront has issued and completed every read of the stage being retired (the second
 // half-step's fragments were all requested during the first) and has seen its own fills of
 // the next stage land; after it the second half-step computes from registers, requests the
-// next stage's first fragments and issues the fills that refill the retired stage, one after
-// every fourth MFMA.
+// next stage's first fragments and issues the fills that refill the retired stage.
 //
 // Persistent workgroups: 256 workgroups, one per CU, each walking tiles l, l + 256, ...; a
 // workgroup's k-steps form ONE stream across its tiles.  The fills of a tile's last two
 // k-steps fetch the first two k-blocks of the workgroup's next tile, so the next tile's first
 // hand-over finds its data there, and the epilogue's stores drain while the next tile
-// computes.  Wall-clock stamps per tile (development build, 13B shapes) of the version that
+// computes.  Wall-clock stamps per tile (development build, 13B shapes) of a version that
 // launched one workgroup per tile: 2.2-2.5 us from a workgroup's start to its first hand-over
 // and 1.2 / 2.6 / 7.4 us (QKV / gate-up / residual GEMMs) between one workgroup's end and the
-// next one's start on the same CU, against 114 us of k-loop per tile at K = 5120; both are
-// gone (the residual GEMMs gained 2 %, gate-up 1.3 %, QKV 1 %).  What remains outside the
-// k-loop is the epilogue itself, with the matrix pipe idle: 3 us (SwiGLU), 9.5 us (RoPE and
-// cache append), 12 us (fp32 residual read-modify-write) per tile.
+// next one's start on the same CU, against 114 us of k-loop per tile at K = 5120.  What remains
+// outside the k-loop is the epilogue itself, with the matrix pipe idle: 4 us (SwiGLU), 10 us
+// (RoPE and cache append), 18 us (fp32 residual read-modify-write) per tile.
 //
-// What bounds the k-loop, from shader-clock stamps around the hand-over (development build): a
-// k-step takes about 2800 cycles at 2.0 GHz where its 256 MFMAs per SIMD need 2048.  On every
-// SIMD the older of the two wavefronts finishes its half of the work after about 1750 cycles,
-// the younger after about 2500; the barrier costs about 150.  Without any fills the same loop
-// takes about 2350 cycles at 2.3 GHz, and what the fills cost is power first (the clock), wall
-// time second: with fills whose lines all hit L2 the loop ran no faster, with a third fewer
-// LDS reads 2 % faster.  Fills that miss L2 did cost wall time until the prefetch below.
+// Fills that miss L2 cost wall time, so every workgroup touches its share of the operand
+// lines one k-step ahead (see the L2 prefetch below).
 //
 // Tile order: the 32 workgroups resident on one XCD (ids congruent modulo 8 land on the same
 // XCD) work on a 4 x 8 patch of neighbouring tiles and share their operand panels through that
@@ -76,12 +86,12 @@ namespace ls {
 namespace {
 
 constexpr int BM = 256, BN = 256, BK = 64;
-constexpr int NWAVE = 8;
+constexpr int NWAVE = 4;
 constexpr int ROWB = BK * 2;               // bytes per tile row
 constexpr int TILE_BYTES = BM * ROWB;      // 32 KB per operand tile
 constexpr int STAGE_BYTES = 2 * TILE_BYTES;
 constexpr int SMEM_BYTES = 2 * STAGE_BYTES;
-constexpr int FI = 4;                      // fill instructions per operand per wavefront and stage
+constexpr int FI = 8;                      // fill instructions per operand per wavefront and stage
 constexpr int PERSISTENT_WGS = 256;        // one workgroup per CU
 constexpr int PF_AHEAD = 1;                // k-steps between the L2 prefetch of a line and its fill
 
@@ -149,20 +159,27 @@ __device__ __forceinline__ bf16x4 to_bf16x4(f32x4 v) {
 
 constexpr int EPI_ROPE = 4;  // EPI_STORE with RoPE and the KV-cache append (QKV projection of a prompt pass)
 
-// Epilogue of one tile.  acc[i][j][r] is C[m0 + 128 wm + 16 i + lane%16][n0 + 64 wn + 16 j + 4 (lane/16) + r].
-template <int EPI>
-__device__ __forceinline__ void store_tile(f32x4 (&acc)[8][4], int m0, int n0, int M, int N, void* __restrict__ outv,
+// Epilogue of one tile, for one 64-column slice of a wavefront's 128 x 128 results: the four
+// fragments accf[i][J0 .. J0 + 3], whose element r is
+// C[m0 + 128 wm + 16 i + lane%16][n0 + 64 wn + 16 j + 4 (lane/16) + r] with wn the slice's
+// number within the tile (0..3) and j = 0..3.
+template <int EPI, int J0>
+__device__ __forceinline__ void store_tile(f32x4 (&accf)[8][8], int m0, int n0, int M, int N, void* __restrict__ outv,
                                            float* __restrict__ resid, const RopeAppend& rp, int wm, int wn, int l16,
                                            int lq) {
+#define acc(i_, j_) accf[i_][J0 + (j_)]
+  // (opaque to the compiler, so that nothing derived from the lane number for this epilogue
+  // is computed before the k-loop and kept in registers through it)
+  asm volatile("" : "+v"(l16), "+v"(lq));
   constexpr bool GLU = (EPI == EPI_SWIGLU);
   const bool vec = (N & 3) == 0;
   if constexpr (EPI == EPI_ROPE) {
-    // A wavefront's 64 columns lie inside one head (head_dim 64 or 128): query, key or value.
+    // The slice's 64 columns lie inside one head (head_dim 64 or 128): query, key or value.
     // A lane's four consecutive columns are two rotation pairs (dims 2p, 2p+1); their
     // (cos, sin) are one 16-byte table load.  The table loads of the next row block are in
     // flight while the current one is rotated and stored.
     const int ncol0 = n0 + wn * 64;
-    if (ncol0 >= N) return;  // N is a multiple of the head size: the whole wavefront is out
+    if (ncol0 >= N) return;  // N is a multiple of the head size: the whole slice is out
     const int head = ncol0 / rp.hd, dd0 = ncol0 - head * rp.hd;
     const bool is_q = head < rp.hq, is_v = head >= rp.hq + rp.hkv;
     const int kh = is_v ? head - rp.hq - rp.hkv : head - rp.hq;
@@ -189,6 +206,7 @@ __device__ __forceinline__ void store_tile(f32x4 (&acc)[8][4], int m0, int n0, i
     LS_TAB_LOAD(0, 0)
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
+      __builtin_amdgcn_sched_barrier(0);  // one row block at a time: the accumulators sit in AGPRs
       if (i + 1 < 8) { LS_TAB_LOAD(i + 1, (i + 1) & 1) }
       const int m = m0 + wm * 128 + i * 16 + l16;
       // a row past the end of the call stores nothing; a row whose sequence has no room left
@@ -198,7 +216,7 @@ __device__ __forceinline__ void store_tile(f32x4 (&acc)[8][4], int m0, int n0, i
       bf16x4 y[4];
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
-        const f32x4 v = acc[i][j];
+        const f32x4 v = acc(i, j);
         const f32x4 t = tab[i & 1][j];  // cos, sin of pair dd/2; cos, sin of pair dd/2 + 1
         // the projection's output is rounded to bf16 first, as the separate rotation kernel sees it
         const float u0 = (float)(bf16)v[0], u1 = (float)(bf16)v[1], u2 = (float)(bf16)v[2], u3 = (float)(bf16)v[3];
@@ -247,7 +265,7 @@ __device__ __forceinline__ void store_tile(f32x4 (&acc)[8][4], int m0, int n0, i
           const int m = m0 + wm * 128 + (i2 + ii) * 16 + l16;
           const int n = n0 + wn * 64 + j * 16 + 4 * lq;
           float* p = resid + (size_t)m * N + n;
-          const f32x4 v = old[ii][j] + acc[i2 + ii][j];
+          const f32x4 v = old[ii][j] + acc(i2 + ii, j);
           if (m < M && vec && n + 3 < N) *reinterpret_cast<f32x4*>(p) = v;
           else
 #pragma unroll
@@ -258,13 +276,14 @@ __device__ __forceinline__ void store_tile(f32x4 (&acc)[8][4], int m0, int n0, i
     return;
   }
   if constexpr (EPI == EPI_STORE || GLU) {
-    // bf16 results, the wavefront's columns all inside the matrix and rows 16-byte aligned:
+    // bf16 results, the slice's columns all inside the matrix and rows 16-byte aligned:
     // 16-byte stores of eight consecutive columns (see side_by_side)
     constexpr int WCOLS = GLU ? 32 : 64;
     const int ncol0 = n0 + wn * WCOLS;
     if ((N & 7) == 0 && ncol0 + WCOLS <= N) {
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
+        __builtin_amdgcn_sched_barrier(0);  // one row block at a time: the accumulators sit in AGPRs
         const int m = m0 + wm * 128 + i * 16 + l16;
         bf16* row = (bf16*)outv + (size_t)min(m, M - 1) * N + ncol0 + 8 * lq;
         if constexpr (GLU) {
@@ -272,13 +291,13 @@ __device__ __forceinline__ void store_tile(f32x4 (&acc)[8][4], int m0, int n0, i
 #pragma unroll
           for (int j = 0; j < 2; ++j)
 #pragma unroll
-            for (int r = 0; r < 4; ++r) g[j][r] = silu_f(acc[i][j][r]) * acc[i][j + 2][r];
+            for (int r = 0; r < 4; ++r) g[j][r] = silu_f(acc(i, j)[r]) * acc(i, j + 2)[r];
           const u32x4 o = side_by_side(to_bf16x4(g[0]), to_bf16x4(g[1]));
           if (m < M) *reinterpret_cast<u32x4*>(row) = o;
         } else {
 #pragma unroll
           for (int jp = 0; jp < 2; ++jp) {
-            const u32x4 o = side_by_side(to_bf16x4(acc[i][2 * jp]), to_bf16x4(acc[i][2 * jp + 1]));
+            const u32x4 o = side_by_side(to_bf16x4(acc(i, 2 * jp)), to_bf16x4(acc(i, 2 * jp + 1)));
             if (m < M) *reinterpret_cast<u32x4*>(row + jp * 32) = o;
           }
         }
@@ -288,6 +307,7 @@ __device__ __forceinline__ void store_tile(f32x4 (&acc)[8][4], int m0, int n0, i
   }
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
+    __builtin_amdgcn_sched_barrier(0);  // one row block at a time: the accumulators sit in AGPRs
     const int m = m0 + wm * 128 + i * 16 + l16;
     if (m >= M) continue;
     if constexpr (GLU) {
@@ -296,7 +316,7 @@ __device__ __forceinline__ void store_tile(f32x4 (&acc)[8][4], int m0, int n0, i
         const int n = n0 + wn * 32 + j * 16 + 4 * lq;
         bf16x4 v;
 #pragma unroll
-        for (int r = 0; r < 4; ++r) v[r] = (bf16)(silu_f(acc[i][j][r]) * acc[i][j + 2][r]);
+        for (int r = 0; r < 4; ++r) v[r] = (bf16)(silu_f(acc(i, j)[r]) * acc(i, j + 2)[r]);
         bf16* p = (bf16*)outv + (size_t)m * N + n;
         if (vec && n + 3 < N) *reinterpret_cast<bf16x4*>(p) = v;
         else
@@ -311,7 +331,7 @@ __device__ __forceinline__ void store_tile(f32x4 (&acc)[8][4], int m0, int n0, i
         if constexpr (EPI == EPI_STORE) {
           bf16x4 v;
 #pragma unroll
-          for (int r = 0; r < 4; ++r) v[r] = (bf16)acc[i][j][r];
+          for (int r = 0; r < 4; ++r) v[r] = (bf16)acc(i, j)[r];
           bf16* p = (bf16*)outv + (size_t)m * N + n;
           if (vec && n + 3 < N) *reinterpret_cast<bf16x4*>(p) = v;
           else
@@ -320,14 +340,56 @@ __device__ __forceinline__ void store_tile(f32x4 (&acc)[8][4], int m0, int n0, i
               if (n + r < N) p[r] = v[r];
         } else {
           float* p = (float*)outv + (size_t)m * N + n;
-          if (vec && n + 3 < N) *reinterpret_cast<f32x4*>(p) = acc[i][j];
+          if (vec && n + 3 < N) *reinterpret_cast<f32x4*>(p) = acc(i, j);
           else
 #pragma unroll
             for (int r = 0; r < 4; ++r)
-              if (n + r < N) p[r] = acc[i][j][r];
+              if (n + r < N) p[r] = acc(i, j)[r];
         }
       }
     }
+  }
+#undef acc
+}
+
+// fp32 read-modify-write of the residual rows for a wavefront's whole 128 x 128 results, 16
+// bytes per lane: the old values of RB row blocks (8 RB loads of 16 bytes per lane) are
+// requested before the first sum is stored; the operand fragments' registers are free by then.
+__device__ __forceinline__ void add_tile_to_residual(f32x4 (&acc)[8][8], int m0, int n0, int M, int N,
+                                                     float* __restrict__ resid, int wm, int wn, int l16, int lq) {
+  constexpr int RB = 4;
+  const bool vec = (N & 3) == 0;
+  asm volatile("" : "+v"(l16), "+v"(lq));  // see store_tile
+#pragma unroll
+  for (int i2 = 0; i2 < 8; i2 += RB) {
+    __builtin_amdgcn_sched_barrier(0);
+    f32x4 old[RB][8];
+#pragma unroll
+    for (int ii = 0; ii < RB; ++ii)
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const int m = m0 + wm * 128 + (i2 + ii) * 16 + l16;
+        const int n = n0 + wn * 128 + j * 16 + 4 * lq;
+        const float* p = resid + (size_t)m * N + n;
+        if (m < M && vec && n + 3 < N) old[ii][j] = *reinterpret_cast<const f32x4*>(p);
+        else
+#pragma unroll
+          for (int r = 0; r < 4; ++r) old[ii][j][r] = (m < M && n + r < N) ? p[r] : 0.f;
+      }
+#pragma unroll
+    for (int ii = 0; ii < RB; ++ii)
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const int m = m0 + wm * 128 + (i2 + ii) * 16 + l16;
+        const int n = n0 + wn * 128 + j * 16 + 4 * lq;
+        float* p = resid + (size_t)m * N + n;
+        const f32x4 v = old[ii][j] + acc[i2 + ii][j];
+        if (m < M && vec && n + 3 < N) *reinterpret_cast<f32x4*>(p) = v;
+        else
+#pragma unroll
+          for (int r = 0; r < 4; ++r)
+            if (m < M && n + r < N) p[r] = v[r];
+      }
   }
 }
 
@@ -340,7 +402,7 @@ k_gemm_mfma(const bf16* __restrict__ A, const bf16* __restrict__ W, int M, int N
   constexpr bool GLU = (EPI == EPI_SWIGLU);
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int wm = wave >> 2, wn = wave & 3;
+  const int wm = wave >> 1, wn = wave & 1;
   const int l16 = lane & 15, lq = lane >> 4;
 
   // ---- workgroup id -> tiles.  256 workgroups, one per CU (a workgroup's LDS fills a CU), each
@@ -359,17 +421,21 @@ k_gemm_mfma(const bf16* __restrict__ A, const bf16* __restrict__ W, int M, int N
   int m0 = ta.tm * BM;
   int n0 = GLU ? ta.tn * (BN / 2) : ta.tn * BN;  // GLU: 128 output columns per tile
 
-  // ---- global -> LDS: wave w fills tile rows 32w..32w+31 of both operands, 8 rows per
-  // instruction; lane l supplies row 32w + 8i + l/8, physical chunk l%8.  Byte offsets from
+  // ---- global -> LDS: wave w fills tile rows 64w..64w+63 of both operands, 8 rows per
+  // instruction; lane l supplies row 64w + 8i + l/8, physical chunk l%8.  Byte offsets from
   // the operand's base (both operands are below 4 GB): the k-block's offset is added to the
   // scalar base, so a fill costs no vector address arithmetic.
   unsigned ao[FI], wo[FI];
   auto fill_offsets = [&](const TileAt& t) {
     const int tm0 = t.tm * BM, tn0 = GLU ? t.tn * (BN / 2) : t.tn * BN;
+    // (the lane number passes through an empty asm statement so that what is derived from it
+    // is computed here, once per tile, instead of living in registers through the k-loop)
+    int ln = lane;
+    asm volatile("" : "+v"(ln));
 #pragma unroll
     for (int i = 0; i < FI; ++i) {
-      const int row = wave * 32 + i * 8 + (lane >> 3);
-      const int c = (lane & 7) ^ ((row >> 1) & 7);
+      const int row = wave * 64 + i * 8 + (ln >> 3);
+      const int c = (ln & 7) ^ ((row >> 1) & 7);
       const int am = min(tm0 + row, M - 1);
       ao[i] = (unsigned)(((size_t)am * K + c * 8) * 2);
       int wrow;
@@ -386,7 +452,7 @@ k_gemm_mfma(const bf16* __restrict__ A, const bf16* __restrict__ W, int M, int N
     }
   };
   fill_offsets(ta);
-  const int fill_off = wave * 32 * ROWB;
+  const int fill_off = wave * 64 * ROWB;
 #define LS_FA(stage_, k0_, i_)                                                                        \
   __builtin_amdgcn_global_load_lds((const void*)((const char*)A + (size_t)(k0_) * 2 + ao[i_]),        \
       (lds_void*)(smem + (stage_) * STAGE_BYTES + fill_off + (i_) * 1024), 16, 0, 0);
@@ -411,17 +477,20 @@ k_gemm_mfma(const bf16* __restrict__ A, const bf16* __restrict__ W, int M, int N
   // activation panel by the 8 of a patch row; whoever asks first waits for HBM or the
   // memory-side cache, and with two LDS stages a fill has one k-step to land.  So every
   // workgroup touches its share of the patch's lines PF_AHEAD k-steps before they are filled:
-  // 64 of the 256 weight rows and 32 of the 256 activation rows, i.e. 8 + 4 lines per wavefront
-  // and k-step, fetched by one 4-byte LDS-direct load (its lanes share those 12 lines; the
+  // 64 of the 256 weight rows and 32 of the 256 activation rows, i.e. 16 + 8 lines per wavefront
+  // and k-step, fetched by one 4-byte LDS-direct load (its lanes share those 24 lines; the
   // words go to a scratch piece of LDS nobody reads).  It is the youngest vector memory
   // operation of the wavefront at every hand-over, which therefore waits for all but one
-  // (vmcnt(1)): vector memory loads return in order.  Measured at the 13B shape: the waits for
-  // fills at the hand-over (300-700 cycles per k-step without it) disappear, +4.4 %.
+  // (vmcnt(1)): vector memory loads return in order.  Measured at the 13B shape (with the
+  // eight-wavefront version): the waits for fills at the hand-over (300-700 cycles per k-step
+  // without it) disappear, +4.4 %.
   // The last k-steps of a tile prefetch the first k-blocks of the workgroup's next tile.
   auto pf_base = [&](const TileAt& t) -> const char* {
-    const int p = (lane & 15) < 12 ? (lane & 15) : (lane & 7);  // 12 distinct lines per wavefront
-    const int row_w = (t.full ? 64 * t.q4 : 0) + 8 * wave + (p & 7);
-    const int row_a = (t.full ? 32 * t.q8 : 0) + 4 * wave + (p & 3);
+    int ln = lane;
+    asm volatile("" : "+v"(ln));
+    const int p = (ln & 31) < 24 ? (ln & 31) : (ln & 15);  // 24 distinct lines per wavefront
+    const int row_w = (t.full ? 64 * t.q4 : 0) + 16 * wave + (p & 15);
+    const int row_a = (t.full ? 32 * t.q8 : 0) + 8 * wave + (p & 7);
     const int tn0 = GLU ? t.tn * (BN / 2) : t.tn * BN;
     int wrow;
     if constexpr (GLU) {
@@ -432,7 +501,7 @@ k_gemm_mfma(const bf16* __restrict__ A, const bf16* __restrict__ W, int M, int N
       wrow = min(tn0 + row_w, N - 1);
     }
     const int am = min(t.tm * BM + row_a, M - 1);
-    return (p < 8) ? (const char*)W + (size_t)wrow * K * 2 : (const char*)A + (size_t)am * K * 2;
+    return (p < 16) ? (const char*)W + (size_t)wrow * K * 2 : (const char*)A + (size_t)am * K * 2;
   };
   const char* pf_ptr = pf_base(ta);
   const char* pf_next = has_next ? pf_base(tb) : pf_ptr;
@@ -441,70 +510,75 @@ k_gemm_mfma(const bf16* __restrict__ A, const bf16* __restrict__ W, int M, int N
       (const void*)((kb_) < KT ? pf_ptr + (size_t)(kb_) * (BK * 2)                                  \
                                : pf_next + (size_t)min((kb_) - KT, KT - 1) * (BK * 2)),             \
       (lds_void*)(smem + SMEM_BYTES), 4, 0, 0);
-  f32x4 acc[8][4];
+  f32x4 acc[8][8];
 #pragma unroll
   for (int i = 0; i < 8; ++i)
 #pragma unroll
-    for (int j = 0; j < 4; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int j = 0; j < 8; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
   // ---- LDS addresses of this lane's fragment reads in stage 0: fragment = 16 tile rows x 32 k,
   // lane -> row lane%16, k-octet lane/16 (first half-step) or 4 + lane/16 (second); later row
-  // blocks are +2048 bytes (the swizzle term depends on row%16 only), stage 1 is +STAGE_BYTES
+  // and column blocks are +2048 bytes (the swizzle term depends on row%16 only), stage 1 is
+  // +STAGE_BYTES
   const unsigned lds0 = (unsigned)(size_t)(lds_void*)smem;
   const unsigned xa0 = lds0 + swz(wm * 128 + l16, lq), xa1 = lds0 + swz(wm * 128 + l16, 4 + lq);
-  const unsigned wa0 = lds0 + TILE_BYTES + swz(wn * 64 + l16, lq);
-  const unsigned wa1 = lds0 + TILE_BYTES + swz(wn * 64 + l16, 4 + lq);
+  const unsigned wa0 = lds0 + TILE_BYTES + swz(wn * 128 + l16, lq);
+  const unsigned wa1 = lds0 + TILE_BYTES + swz(wn * 128 + l16, 4 + lq);
   const int KT = K / BK;
 
-  bf16x8 xf[6], xe[2][2], wf[2][4];
+  bf16x8 xf[2][8], wf[2][8];
 #define LS_SB() __builtin_amdgcn_sched_barrier(0);
 #define LS_RD(dst_, addr_, off_) \
   asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst_) : "v"(addr_), "n"(off_));
   // wait until at most n_ of this wavefront's LDS reads are outstanding (other counters untouched)
 #define LS_WAITL(n_) __builtin_amdgcn_s_waitcnt(0xC07F | ((n_) << 8));
-  // activation fragment of row block i_ in half-step parity ws_: blocks 0..5 live in one set of
-  // registers, blocks 6 and 7 in two (see below)
-#define LS_X(ws_, i_) ((i_) < 6 ? xf[(i_) < 6 ? (i_) : 0] : xe[ws_][(i_) < 6 ? 0 : (i_) - 6])
 #define LS_MF(ws_, i_, j_) \
-  acc[i_][j_] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[ws_][j_], LS_X(ws_, i_), acc[i_][j_], 0, 0, 0);
+  acc[i_][j_] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[ws_][j_], xf[ws_][i_], acc[i_][j_], 0, 0, 0);
 #define LS_NONE
-  // One row block of a half-step: four MFMAs; after the second the reads WR_ (the next
-  // half-step's weight fragment i_, row blocks 0..3 only), after the third an optional fill
-  // (F_), after the fourth the read XR_ (the row block's own activation fragment for the next
-  // half-step, row blocks 0..5).
-#define LS_BLOCK(ws_, i_, WR_, F_, XR_)                             \
-  LS_MF(ws_, i_, 0) LS_SB()                                         \
-  LS_MF(ws_, i_, 1) LS_SB()                                         \
-  WR_ LS_SB()                                                       \
-  LS_MF(ws_, i_, 2) LS_SB()                                         \
-  F_ LS_SB()                                                        \
-  LS_MF(ws_, i_, 3) LS_SB()                                         \
-  XR_ LS_SB()
-  // A half-step.  The fragments of row blocks 6 and 7 are double buffered and requested early
-  // (with the weight fragments of row blocks 2 and 3), so that the last read before the
-  // hand-over barrier is eight MFMAs old when the barrier waits for it.  Reads are issued in
-  // the order W0' X0' W1' X1' W2' X6' X2' W3' X7' X3' X4' X5' (primes: for the next half-step).
-  // Row block 0 needs X0 and all of W0..W3, i.e. the first eight reads of the previous
-  // half-step: four younger ones may be outstanding.  Row blocks 1 and 2 are covered by that
-  // wait.  Row block 3 needs X3, the tenth: two younger ones of the previous half-step plus the
-  // seven issued so far in this one.  Row block 4 needs the eleventh: one younger plus ten of
-  // this half-step; row block 5 the twelfth: none plus eleven.  Row blocks 6 and 7 need the
-  // sixth and the ninth, which the waits of row blocks 0 and 3 have covered.
-#define LS_HALF(ws_, xaddr_, waddr_, F0, F1, F2, F3, F4, F5, F6, F7)                                   \
-  LS_WAITL(4) LS_SB()                                                                                  \
-  LS_BLOCK(ws_, 0, LS_RD(wf[(ws_) ^ 1][0], waddr_, 0 * 2048), F0, LS_RD(xf[0], xaddr_, 0 * 2048))      \
-  LS_BLOCK(ws_, 1, LS_RD(wf[(ws_) ^ 1][1], waddr_, 1 * 2048), F1, LS_RD(xf[1], xaddr_, 1 * 2048))      \
-  LS_BLOCK(ws_, 2, LS_RD(wf[(ws_) ^ 1][2], waddr_, 2 * 2048) LS_RD(xe[(ws_) ^ 1][0], xaddr_, 6 * 2048), \
-           F2, LS_RD(xf[2], xaddr_, 2 * 2048))                                                         \
-  LS_WAITL(9) LS_SB()                                                                                  \
-  LS_BLOCK(ws_, 3, LS_RD(wf[(ws_) ^ 1][3], waddr_, 3 * 2048) LS_RD(xe[(ws_) ^ 1][1], xaddr_, 7 * 2048), \
-           F3, LS_RD(xf[3], xaddr_, 3 * 2048))                                                         \
-  LS_WAITL(11) LS_SB()                                                                                 \
-  LS_BLOCK(ws_, 4, LS_NONE, F4, LS_RD(xf[4], xaddr_, 4 * 2048))                                        \
-  LS_WAITL(11) LS_SB()                                                                                 \
-  LS_BLOCK(ws_, 5, LS_NONE, F5, LS_RD(xf[5], xaddr_, 5 * 2048))                                        \
-  LS_BLOCK(ws_, 6, LS_NONE, F6, LS_NONE)                                                               \
-  LS_BLOCK(ws_, 7, LS_NONE, F7, LS_NONE)
+  // two MFMAs, then one memory instruction (or none)
+#define LS_MM(ws_, i_, j_, OP_) LS_MF(ws_, i_, j_) LS_SB() LS_MF(ws_, i_, (j_) + 1) LS_SB() OP_ LS_SB()
+  // one row block of a half-step: eight MFMAs, a memory instruction after every second
+#define LS_ROWB(ws_, i_, O0, O1, O2, O3) \
+  LS_MM(ws_, i_, 0, O0) LS_MM(ws_, i_, 2, O1) LS_MM(ws_, i_, 4, O2) LS_MM(ws_, i_, 6, O3)
+  // The fragments of a half-step are requested during the half-step before it, into the other
+  // register set, always in the order W0 .. W7, X0 .. X7; LDS reads return in order.
+  // First half-step of a k-step: its fragments were requested during the previous second
+  // half-step, two per row block; the second half-step's fragments (k-octets 4..7 of the same
+  // stage) are requested during row blocks 0..3, four per row block, so that the last of them
+  // is 32 MFMAs old at the hand-over.  Row block 0 needs W0..W7 and X0: seven younger reads may
+  // be outstanding.  Row block i needs X_i: 7 - i older-issued ones plus the 4 i requested in
+  // this half-step so far, at most 15 (the counter's range; from row block 4 on the wait for
+  // "at most 15" already covers X4..X7).
+#define LS_HALF0(xaddr_, waddr_)                                                                          \
+  LS_WAITL(7) LS_SB()                                                                                     \
+  LS_ROWB(0, 0, LS_RD(wf[1][0], waddr_, 0 * 2048), LS_RD(wf[1][1], waddr_, 1 * 2048),                     \
+          LS_RD(wf[1][2], waddr_, 2 * 2048), LS_RD(wf[1][3], waddr_, 3 * 2048))                           \
+  LS_WAITL(10) LS_SB()                                                                                    \
+  LS_ROWB(0, 1, LS_RD(wf[1][4], waddr_, 4 * 2048), LS_RD(wf[1][5], waddr_, 5 * 2048),                     \
+          LS_RD(wf[1][6], waddr_, 6 * 2048), LS_RD(wf[1][7], waddr_, 7 * 2048))                           \
+  LS_WAITL(13) LS_SB()                                                                                    \
+  LS_ROWB(0, 2, LS_RD(xf[1][0], xaddr_, 0 * 2048), LS_RD(xf[1][1], xaddr_, 1 * 2048),                     \
+          LS_RD(xf[1][2], xaddr_, 2 * 2048), LS_RD(xf[1][3], xaddr_, 3 * 2048))                           \
+  LS_WAITL(15) LS_SB()                                                                                    \
+  LS_ROWB(0, 3, LS_RD(xf[1][4], xaddr_, 4 * 2048), LS_RD(xf[1][5], xaddr_, 5 * 2048),                     \
+          LS_RD(xf[1][6], xaddr_, 6 * 2048), LS_RD(xf[1][7], xaddr_, 7 * 2048))                           \
+  LS_WAITL(15) LS_SB()                                                                                    \
+  LS_ROWB(0, 4, LS_NONE, LS_NONE, LS_NONE, LS_NONE)                                                       \
+  LS_ROWB(0, 5, LS_NONE, LS_NONE, LS_NONE, LS_NONE)                                                       \
+  LS_ROWB(0, 6, LS_NONE, LS_NONE, LS_NONE, LS_NONE)                                                       \
+  LS_ROWB(0, 7, LS_NONE, LS_NONE, LS_NONE, LS_NONE)
+  // Second half-step: its fragments all arrived before the hand-over.  Per row block two
+  // requests for the next k-step's first half-step (k-octets 0..3 of the other stage) and two
+  // fills of the retired stage; the L2 prefetch goes last.
+#define LS_HALF1(xaddr_, waddr_, stage_, k2_, PF_)                                                        \
+  LS_ROWB(1, 0, LS_RD(wf[0][0], waddr_, 0 * 2048), LS_FA(stage_, k2_, 0), LS_RD(wf[0][1], waddr_, 1 * 2048), LS_FW(stage_, k2_, 0)) \
+  LS_ROWB(1, 1, LS_RD(wf[0][2], waddr_, 2 * 2048), LS_FA(stage_, k2_, 1), LS_RD(wf[0][3], waddr_, 3 * 2048), LS_FW(stage_, k2_, 1)) \
+  LS_ROWB(1, 2, LS_RD(wf[0][4], waddr_, 4 * 2048), LS_FA(stage_, k2_, 2), LS_RD(wf[0][5], waddr_, 5 * 2048), LS_FW(stage_, k2_, 2)) \
+  LS_ROWB(1, 3, LS_RD(wf[0][6], waddr_, 6 * 2048), LS_FA(stage_, k2_, 3), LS_RD(wf[0][7], waddr_, 7 * 2048), LS_FW(stage_, k2_, 3)) \
+  LS_ROWB(1, 4, LS_RD(xf[0][0], xaddr_, 0 * 2048), LS_FA(stage_, k2_, 4), LS_RD(xf[0][1], xaddr_, 1 * 2048), LS_FW(stage_, k2_, 4)) \
+  LS_ROWB(1, 5, LS_RD(xf[0][2], xaddr_, 2 * 2048), LS_FA(stage_, k2_, 5), LS_RD(xf[0][3], xaddr_, 3 * 2048), LS_FW(stage_, k2_, 5)) \
+  LS_ROWB(1, 6, LS_RD(xf[0][4], xaddr_, 4 * 2048), LS_FA(stage_, k2_, 6), LS_RD(xf[0][5], xaddr_, 5 * 2048), LS_FW(stage_, k2_, 6)) \
+  LS_ROWB(1, 7, LS_RD(xf[0][6], xaddr_, 6 * 2048), LS_FA(stage_, k2_, 7), LS_RD(xf[0][7], xaddr_, 7 * 2048), LS_FW(stage_, k2_, 7) PF_)
   // own LDS reads done, own fills landed, then everyone
 #define LS_HANDOVER(imm_)                    \
   asm volatile("" ::: "memory");             \
@@ -517,17 +591,20 @@ k_gemm_mfma(const bf16* __restrict__ A, const bf16* __restrict__ W, int M, int N
   // first fragments of a tile: k-octets 0..3 of the stage at byte offset so_
 #define LS_FIRST_READS(so_)                                                                            \
   LS_SB()                                                                                              \
-  LS_RD(wf[0][0], wa0 + (so_), 0 * 2048) LS_RD(xf[0], xa0 + (so_), 0 * 2048)                           \
-  LS_RD(wf[0][1], wa0 + (so_), 1 * 2048) LS_RD(xf[1], xa0 + (so_), 1 * 2048)                           \
-  LS_RD(wf[0][2], wa0 + (so_), 2 * 2048) LS_RD(xe[0][0], xa0 + (so_), 6 * 2048) LS_RD(xf[2], xa0 + (so_), 2 * 2048) \
-  LS_RD(wf[0][3], wa0 + (so_), 3 * 2048) LS_RD(xe[0][1], xa0 + (so_), 7 * 2048) LS_RD(xf[3], xa0 + (so_), 3 * 2048) \
-  LS_RD(xf[4], xa0 + (so_), 4 * 2048) LS_RD(xf[5], xa0 + (so_), 5 * 2048)                              \
+  LS_RD(wf[0][0], wa0 + (so_), 0 * 2048) LS_RD(wf[0][1], wa0 + (so_), 1 * 2048)                        \
+  LS_RD(wf[0][2], wa0 + (so_), 2 * 2048) LS_RD(wf[0][3], wa0 + (so_), 3 * 2048)                        \
+  LS_RD(wf[0][4], wa0 + (so_), 4 * 2048) LS_RD(wf[0][5], wa0 + (so_), 5 * 2048)                        \
+  LS_RD(wf[0][6], wa0 + (so_), 6 * 2048) LS_RD(wf[0][7], wa0 + (so_), 7 * 2048)                        \
+  LS_RD(xf[0][0], xa0 + (so_), 0 * 2048) LS_RD(xf[0][1], xa0 + (so_), 1 * 2048)                        \
+  LS_RD(xf[0][2], xa0 + (so_), 2 * 2048) LS_RD(xf[0][3], xa0 + (so_), 3 * 2048)                        \
+  LS_RD(xf[0][4], xa0 + (so_), 4 * 2048) LS_RD(xf[0][5], xa0 + (so_), 5 * 2048)                        \
+  LS_RD(xf[0][6], xa0 + (so_), 6 * 2048) LS_RD(xf[0][7], xa0 + (so_), 7 * 2048)                        \
   LS_SB()
-
-  // ---- prologue: prefetch, hand over stage 0 (the eight fills of stage 1 and the prefetch may
-  // still be in flight: vmcnt(9)), first fragments
+  // ---- prologue: prefetch, hand over stage 0 (the sixteen fills of stage 1 and the prefetch
+  // may still be in flight: vmcnt(17), whose upper bits sit in bits 15:14 of the immediate),
+  // first fragments
   LS_PREFETCH(1 + PF_AHEAD)
-  LS_HANDOVER(0x0079)
+  LS_HANDOVER(0x4071)
   LS_FIRST_READS(0u)
 
   // The workgroup's k-steps form one stream across its tiles: stage = (k-steps so far) & 1, and
@@ -543,7 +620,7 @@ k_gemm_mfma(const bf16* __restrict__ A, const bf16* __restrict__ W, int M, int N
       {
         const unsigned xa = xa1 + sx, wa = wa1 + sx;
         LS_SB()
-        LS_HALF(0, xa, wa, LS_NONE, LS_NONE, LS_NONE, LS_NONE, LS_NONE, LS_NONE, LS_NONE, LS_NONE)
+        LS_HALF0(xa, wa)
       }
       // vmcnt(1): all fills, not the youngest prefetch.  (Right after an epilogue this also waits
       // for all but the last of its stores; a hand-over that lets them pass, with the fills
@@ -557,6 +634,9 @@ k_gemm_mfma(const bf16* __restrict__ A, const bf16* __restrict__ W, int M, int N
           // very last tile fills the retired stage once more with its last k-block (lines that
           // are in L2 anyway) instead of branching around every fill
           if (has_next) {
+            // (computed here, from two scalars, rather than a whole tile ahead of their use:
+            // the compiler would otherwise keep sixteen more registers alive through the k-loop)
+            asm volatile("" : "+s"(tb.tm), "+s"(tb.tn));
             fill_offsets(tb);
             kf = 0;
           } else {
@@ -567,8 +647,7 @@ k_gemm_mfma(const bf16* __restrict__ A, const bf16* __restrict__ W, int M, int N
         const int k2 = kf * BK;
         ++kf;
         LS_SB()
-        LS_HALF(1, xa, wa, LS_FA(buf, k2, 0), LS_FW(buf, k2, 0), LS_FA(buf, k2, 1), LS_FW(buf, k2, 1), LS_FA(buf, k2, 2),
-                LS_FW(buf, k2, 2), LS_FA(buf, k2, 3), LS_FW(buf, k2, 3) LS_PREFETCH(kt + 2 + PF_AHEAD))
+        LS_HALF1(xa, wa, buf, k2, LS_PREFETCH(kt + 2 + PF_AHEAD))
       }
     }
     // the fragments requested by the last half-step land in registers the epilogue may reuse:
@@ -576,7 +655,12 @@ k_gemm_mfma(const bf16* __restrict__ A, const bf16* __restrict__ W, int M, int N
     LS_SB()
     LS_WAITL(0)
     LS_SB()
-    store_tile<EPI>(acc, m0, n0, M, N, outv, resid, rp, wm, wn, l16, lq);
+    if constexpr (EPI == EPI_RESID) {
+      add_tile_to_residual(acc, m0, n0, M, N, resid, wm, wn, l16, lq);
+    } else {
+      store_tile<EPI, 0>(acc, m0, n0, M, N, outv, resid, rp, wm, 2 * wn, l16, lq);
+      store_tile<EPI, 4>(acc, m0, n0, M, N, outv, resid, rp, wm, 2 * wn + 1, l16, lq);
+    }
     if (!has_next) break;
     l += PERSISTENT_WGS;
     ta = tb;
@@ -589,7 +673,7 @@ k_gemm_mfma(const bf16* __restrict__ A, const bf16* __restrict__ W, int M, int N
 #pragma unroll
     for (int i = 0; i < 8; ++i)
 #pragma unroll
-      for (int j = 0; j < 4; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+      for (int j = 0; j < 8; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
     // the new tile's first k-block landed before the hand-over of the last k-step
     LS_FIRST_READS((unsigned)(gk & 1) * STAGE_BYTES)
   }
@@ -604,10 +688,11 @@ k_gemm_mfma(const bf16* __restrict__ A, const bf16* __restrict__ W, int M, int N
 #undef LS_RD
 #undef LS_WAITL
 #undef LS_MF
-#undef LS_X
 #undef LS_NONE
-#undef LS_BLOCK
-#undef LS_HALF
+#undef LS_MM
+#undef LS_ROWB
+#undef LS_HALF0
+#undef LS_HALF1
 #undef LS_HANDOVER
 #undef LS_PREFETCH
 
