@@ -34,9 +34,14 @@
 // One wavefront per SIMD has nobody to wait for (all four arrive within 20 cycles of each
 // other), reads a third fewer operand bytes from LDS per multiply-add, and its k-loop took
 // 109.5 us per 256 x 256 x 5120 tile against 114.5; what it loses is the second wavefront that
-// covered the issue slots of the fill instructions (about 12 cycles of an idle matrix pipe per
-// global_load_lds, 200 of a k-step's 2740 cycles; a k-step's 128 MFMAs need 2048) and half of
-// the memory-level parallelism in the epilogues.
+// covered the issue slots of the memory instructions and half of the memory-level parallelism
+// in the epilogues.  With one wavefront per SIMD every instruction between two MFMAs costs the
+// matrix pipe its own issue time: a k-step's 128 MFMAs need 2048 cycles and take 2250 with the
+// LDS reads alone (about 5 cycles per ds_read_b128), 2460 with the fills (about 12 per
+// global_load_lds), 2740 with the hand-over.  (Measured without effect: four fills sharing one
+// LDS base in M0 through the instruction's immediate offset, which removes twelve scalar
+// writes and wait states per k-step; starting the eight XCDs a few microseconds apart so that
+// their epilogues do not ask for HBM at the same time.)
 //
 // The k-loop is written out in issue order.  A k-step is two half-steps of 64 MFMAs (k = 32
 // each).  The LDS reads are inline assembly and the waits for them are explicit
