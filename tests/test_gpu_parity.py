@@ -154,6 +154,20 @@ def test_prompt_gemm_workgroups_that_walk_several_tiles():
         gpu.close()
 
 
+@pytest.mark.parametrize("shape,n_seq", [(MINI_BF16, 70), (MINI_BF16_HD128.with_(vocab=1000), 130)])
+def test_more_than_64_sequences(shape, n_seq):
+    """Beyond 64 rows a decode step leaves the weight-streaming GEMMs for the prompt pass's MFMA
+    GEMM (one ragged tile row), the rotation kernel runs on its own, and the LM head of both
+    passes is the MFMA GEMM's fp32 store."""
+    rng = np.random.default_rng(83)
+    lengths = [int(n) for n in rng.integers(1, 13, size=n_seq)]
+    errs, agree = run_full_model(shape, 83, lengths, 3)
+    assert max(errs) <= TOL["bf16"], errs
+    adj = sum(a[1] for a in agree)
+    n = sum(a[2] for a in agree)
+    assert adj >= 0.99 * n, agree
+
+
 def test_split_stages_equal_whole_stage():
     """Running layers [0,k) then [k,L) as two stages equals one stage [0,L)."""
     shape, seed, lengths = MINI_BF16.with_(vocab=0), 5, [33, 8]
