@@ -357,6 +357,29 @@ __device__ __forceinline__ void store_tile(f32x4 (&accf)[8][8], int m0, int n0, 
 #undef acc
 }
 
+// fp32 store of a wavefront's whole 128 x 128 results (the LM head's logits), 16 bytes per lane.
+__device__ __forceinline__ void store_tile_f32(f32x4 (&acc)[8][8], int m0, int n0, int M, int N,
+                                               float* __restrict__ out, int wm, int wn, int l16, int lq) {
+  const bool vec = (N & 3) == 0;
+  asm volatile("" : "+v"(l16), "+v"(lq));  // see store_tile
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    __builtin_amdgcn_sched_barrier(0);  // one row block at a time: the accumulators sit in AGPRs
+    const int m = m0 + wm * 128 + i * 16 + l16;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const int n = n0 + wn * 128 + j * 16 + 4 * lq;
+      float* p = out + (size_t)min(m, M - 1) * N + n;
+      const f32x4 v = acc[i][j];
+      if (m < M && vec && n + 3 < N) *reinterpret_cast<f32x4*>(p) = v;
+      else
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+          if (m < M && n + r < N) p[r] = v[r];
+    }
+  }
+}
+
 // fp32 read-modify-write of the residual rows for a wavefront's whole 128 x 128 results, 16
 // bytes per lane: the old values of RB row blocks (8 RB loads of 16 bytes per lane) are
 // requested before the first sum is stored; the operand fragments' registers are free by then.
@@ -662,6 +685,8 @@ k_gemm_mfma(const bf16* __restrict__ A, const bf16* __restrict__ W, int M, int N
     LS_SB()
     if constexpr (EPI == EPI_RESID) {
       add_tile_to_residual(acc, m0, n0, M, N, resid, wm, wn, l16, lq);
+    } else if constexpr (EPI == EPI_F32) {
+      store_tile_f32(acc, m0, n0, M, N, (float*)outv, wm, wn, l16, lq);
     } else {
       store_tile<EPI, 0>(acc, m0, n0, M, N, outv, resid, rp, wm, 2 * wn, l16, lq);
       store_tile<EPI, 4>(acc, m0, n0, M, N, outv, resid, rp, wm, 2 * wn + 1, l16, lq);
